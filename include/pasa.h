@@ -1,0 +1,146 @@
+/*
+ * pasa.h -- C ABI of the MI355X (gfx950) implementation of the PASA sparse self-attention forward
+ * ("Ride the Wave: Precision-Allocated Sparse Attention for Smooth Video Generation").
+ *
+ * The forward runs in four stages, each an entry point of its own so that a caller (and a checker)
+ * can see every intermediate:
+ *
+ *   pasa_block_score      block-pooled Q/K routing logits             (Eq.8 without its row softmax)
+ *   pasa_route            seeded stochastic top-k block selection     (Eq.2 + Sec. "Stochastic Routing")
+ *   pasa_sparse_attn_fwd  exact attention over the selected blocks + grouped Taylor approximation
+ *                         of the unselected ones under one normaliser (Eq.7, Eq.4, Eq.5, Eq.12, Eq.14)
+ *   pasa_attn_dense_ref   dense attention with the same tile machinery (Eq.1)
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer unless marked "host".  The caller owns every buffer; the
+ *     library never allocates, frees or synchronises.  All work is enqueued on `stream`
+ *     (a hipStream_t passed as void*; NULL = the default stream) and is asynchronous.
+ *   - Q, K, V, O are bf16 (uint16 storage), logical shape [B, H, n, d], innermost dimension
+ *     contiguous, the others addressed by the element strides of pasa_shape_t.  d in {64, 128};
+ *     block in {64, 128}.  n need not be a multiple of block: the last block is short, no token
+ *     >= n is ever read or written.  N_B = ceil(n / block) for queries and keys alike.
+ *   - bh = batch * H + head indexes every per-head array.
+ *   - Return value: PASA_OK (0) or a negative pasa_status.  Arguments are validated on the host
+ *     before anything is launched; on error nothing has been enqueued.  A launch failure is
+ *     reported as PASA_EHIP (hipGetLastError after the launch; never a device synchronise).
+ *   - Outputs must not alias inputs.  Base pointers must be 16-byte aligned and strides multiples of
+ *     8 elements (PASA_EALIGN otherwise).
+ *   - Results are deterministic: no atomics, fixed reduction order; the same inputs give the same
+ *     bits on every call.
+ */
+#ifndef PASA_H_
+#define PASA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PASA_API __attribute__((visibility("default")))
+
+typedef enum {
+  PASA_OK = 0,
+  PASA_EINVAL = -1,       /* null pointer, non-positive size, ratio outside (0,1], k outside [1,N_B] */
+  PASA_EUNSUPPORTED = -2, /* d, block or group not supported                                          */
+  PASA_EWORKSPACE = -3,   /* workspace smaller than pasa_*_workspace_bytes says                        */
+  PASA_EALIGN = -4,       /* pointer not 16-byte aligned / stride not a multiple of 8 elements         */
+  PASA_EHIP = -5          /* the HIP runtime refused a launch                                          */
+} pasa_status;
+
+typedef struct {
+  int32_t B, H; /* batch, heads                                                                   */
+  int32_t n;    /* tokens (queries = keys: self-attention)                                        */
+  int32_t d;    /* head dimension, 64 or 128                                                      */
+  int32_t block; /* tokens per block, 64 or 128 (Sec. "Taylor Expansion Approximation")           */
+  int32_t group; /* key blocks per first-order group (Sec. "Grouped First-Order Approximation":
+                    32).  >= N_B: one global matrix (Eq.6).  0: approximation off, unselected blocks
+                    are dropped.  Otherwise a multiple of 32 or a power of two below 32.
+                    Ignored by pasa_block_score and pasa_attn_dense_ref.                          */
+  int64_t stride_b, stride_h, stride_n; /* element strides of Q, K, V and O; d is contiguous     */
+  float scale; /* logit scale; 0 means 1/sqrt(d) (Eq.1)                                          */
+} pasa_shape_t;
+
+/* host-only. */
+PASA_API const char* pasa_strerror(int status);
+
+/* host-only.  k = clamp(floor(keep_ratio * n_blocks + 0.5), 1, n_blocks): the number of key blocks
+ * computed exactly per query block for a "top-k density" keep_ratio (Sec. "Curvature-Aware Dynamic
+ * Budgeting"; the rounding rule is this library's).  Returns PASA_EINVAL (negative) if n_blocks < 1
+ * or keep_ratio is not in (0, 1]. */
+PASA_API int32_t pasa_topk_count(int32_t n_blocks, double keep_ratio);
+
+/* host-only.  N_B of a shape, or a negative status if the shape is invalid. */
+PASA_API int32_t pasa_num_blocks(const pasa_shape_t* shape);
+
+/* host-only.  Number of uint32 words of one row of the selection bitmap: ceil(N_B / 32). */
+PASA_API int32_t pasa_mask_words(int32_t n_blocks);
+
+/* host-only.  Bytes of scratch pasa_block_score needs (pooled Q and K in fp32); 0 on a bad shape. */
+PASA_API size_t pasa_score_workspace_bytes(const pasa_shape_t* shape);
+
+/* host-only.  Bytes of scratch pasa_sparse_attn_fwd and pasa_attn_dense_ref need (key/value block
+ * statistics and re-laid-out operands); 0 on a bad shape. */
+PASA_API size_t pasa_attn_workspace_bytes(const pasa_shape_t* shape);
+
+/*
+ * Stage 1 -- block-pooled scoring (Sec. "Taylor Expansion Approximation", Eq.8).
+ *   scores[bh, i, j] = mean(Q block i) . mean(K block j) * scale + key_bias[bh, j]
+ * Means are over the valid tokens of a block.  Eq.8's softmax over j is monotone per row and is
+ * not applied: routing works on the logits.
+ *   q, k      bf16 [B,H,n,d] (shape strides)
+ *   key_bias  fp32 [B*H, N_B] or NULL (the covariance prior of Eq.8 enters here)
+ *   scores    fp32 [B*H, N_B, N_B] contiguous (out)
+ *   ws        scratch of pasa_score_workspace_bytes(shape) bytes, 256-byte aligned
+ */
+PASA_API int pasa_block_score(const void* q, const void* k, const pasa_shape_t* shape, const float* key_bias,
+                     float* scores, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Stage 2 -- top-k routing with a seeded stochastic selection bias (Eq.2; Sec. "Stochastic Routing").
+ *   r[bh,i,j] = fmaf(noise_amp, w, scores[bh,i,j]) in binary32 (one rounding), where w in [-1,1) is
+ *   ((int32)u >> 8) * 2^-23 and u is word (j & 3) of Philox4x32-10(counter = (j >> 2, i, bh, 0),
+ *   key = (seed & 0xffffffff, seed >> 32)).  Row (bh, i) selects the k_sel largest r under the strict
+ *   order "larger value first (-0 == +0), then smaller j first".  NaN scores are a caller error.
+ *   A fresh seed per layer and denoising step gives the independent re-sampling the paper describes.
+ *   scores  fp32 [BH, N_B, N_B]
+ *   idx     int32 [BH, N_B, k_sel] (out): selected key blocks of each query block, ascending
+ *   mask    uint32 [BH, N_B, ceil(N_B/32)] (out, may be NULL): bit (j & 31) of word (j >> 5) is set
+ *           iff key block j is selected; bits >= N_B are zero
+ * The output is a pure function of (score bits, k_sel, seed, noise_amp).
+ */
+PASA_API int pasa_route(const float* scores, int32_t BH, int32_t n_blocks, int32_t k_sel, uint64_t seed,
+               float noise_amp, int32_t* idx, uint32_t* mask, void* stream);
+
+/*
+ * Stages 3 and 4 -- piecewise attention (Eq.7 with the grouped first-order term of Eq.14).
+ * For query token t of query block i, q~ = Q_t * scale, S = idx[bh, i, :], U = the other blocks:
+ *   Num = sum_{j in S} sum_{n < b_j} exp(q~ K_{j,n}) V_{j,n}
+ *       + sum_{j in U} a_j VS_j,            a_j = exp(q~ Kbar_j), VS_j = sum_n V_{j,n}     (Eq.4)
+ *       + sum_g (sum_{j in U and in group g} a_j) (q~ Hg_g)                                  (Eq.14)
+ *   Den = sum_{j in S} sum_{n < b_j} exp(q~ K_{j,n}) + sum_{j in U} b_j a_j
+ *   O_t = Num / Den   (one online-softmax normaliser; b_j = valid tokens of block j)
+ * with Hg_g the mean over the blocks of group g of H_j = sum_n (K_{j,n} - Kbar_j)^T V_{j,n}
+ * (Eq.5, Eq.12).  The key/value statistics are recomputed by every call (they depend on K and V only).
+ *   idx    int32 [BH, N_B, k_sel], each row strictly ascending, values in [0, N_B) (not checked)
+ *   mask   the bitmap pasa_route wrote for the same idx (required unless shape->group == 0)
+ *   out    bf16 [B,H,n,d] (shape strides)
+ *   lse    fp32 [BH, n] or NULL: log(Den) including the subtracted maximum
+ *   ws     scratch of pasa_attn_workspace_bytes(shape) bytes, 256-byte aligned
+ */
+PASA_API int pasa_sparse_attn_fwd(const void* q, const void* k, const void* v, const pasa_shape_t* shape,
+                         const int32_t* idx, const uint32_t* mask, int32_t k_sel, void* out,
+                         float* lse, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Dense attention, Eq.1: O = softmax(Q K^T * scale) V, same kernels with every block selected.
+ *   out bf16 [B,H,n,d]; lse fp32 [BH, n] or NULL; ws as for pasa_sparse_attn_fwd.
+ */
+PASA_API int pasa_attn_dense_ref(const void* q, const void* k, const void* v, const pasa_shape_t* shape,
+                        void* out, float* lse, void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PASA_H_ */

@@ -1,0 +1,203 @@
+// C ABI of the PASA forward (see include/pasa.h): argument validation, workspace carving, launches.
+// Nothing here allocates, frees or synchronises.
+#include "pasa.h"
+#include "pasa_kernels.hpp"
+
+#include <math.h>
+
+namespace {
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_shape(const pasa_shape_t* s) {
+  if (!s) return PASA_EINVAL;
+  if (s->B < 1 || s->H < 1 || s->n < 1) return PASA_EINVAL;
+  if ((int64_t)s->B * s->H > 65535) return PASA_EUNSUPPORTED;
+  if (s->d != 64 && s->d != 128) return PASA_EUNSUPPORTED;
+  if (s->block != 64 && s->block != 128) return PASA_EUNSUPPORTED;
+  if (!(s->scale >= 0.f) || isinf(s->scale)) return PASA_EINVAL;
+  if (s->stride_n < s->d || s->stride_h < 1 || s->stride_b < 1) return PASA_EINVAL;
+  if ((s->stride_n % 8) || (s->stride_h % 8) || (s->stride_b % 8)) return PASA_EALIGN;
+  return PASA_OK;
+}
+
+int num_blocks(const pasa_shape_t* s) { return (s->n + s->block - 1) / s->block; }
+
+int check_group(int group, int nb) {
+  if (group < 0) return PASA_EINVAL;
+  if (group == 0 || group >= nb) return PASA_OK;
+  if (group % 32 == 0) return PASA_OK;
+  if (group < 32 && (group & (group - 1)) == 0) return PASA_OK;
+  return PASA_EUNSUPPORTED;
+}
+
+float effective_scale(const pasa_shape_t* s) { return s->scale > 0.f ? s->scale : 1.0f / sqrtf((float)s->d); }
+
+struct AttnWorkspace {
+  size_t kbar, vs, hg, partial, total;
+  int n_groups, unit, n_units;
+};
+
+AttnWorkspace carve_attn(const pasa_shape_t* s) {
+  AttnWorkspace w{};
+  const int nb = num_blocks(s);
+  const size_t bh = (size_t)s->B * s->H;
+  if (s->group <= 0) return w;  // no statistics needed
+  const int group = s->group >= nb ? nb : s->group;
+  w.n_groups = (nb + group - 1) / group;
+  w.unit = group < 32 ? group : 32;
+  w.n_units = (nb + w.unit - 1) / w.unit;
+  size_t off = 0;
+  w.kbar = off; off = align_up(off + bh * nb * s->d * 2);
+  w.vs = off; off = align_up(off + bh * nb * s->d * 2);
+  w.hg = off; off = align_up(off + bh * w.n_groups * s->d * s->d * 2);
+  w.partial = off; off = align_up(off + bh * w.n_units * s->d * s->d * 4);
+  w.total = off;
+  return w;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* pasa_strerror(int status) {
+  switch (status) {
+    case PASA_OK: return "ok";
+    case PASA_EINVAL: return "invalid argument";
+    case PASA_EUNSUPPORTED: return "unsupported head dimension, block size, group size or problem size";
+    case PASA_EWORKSPACE: return "workspace too small";
+    case PASA_EALIGN: return "pointer or stride not sufficiently aligned";
+    case PASA_EHIP: return "HIP launch failure";
+    default: return "unknown status";
+  }
+}
+
+int32_t pasa_topk_count(int32_t n_blocks, double keep_ratio) {
+  if (n_blocks < 1 || !(keep_ratio > 0.0) || keep_ratio > 1.0) return PASA_EINVAL;
+  double x = floor(keep_ratio * (double)n_blocks + 0.5);
+  if (x < 1.0) x = 1.0;
+  if (x > (double)n_blocks) x = (double)n_blocks;
+  return (int32_t)x;
+}
+
+int32_t pasa_num_blocks(const pasa_shape_t* shape) {
+  const int rc = check_shape(shape);
+  return rc != PASA_OK ? rc : num_blocks(shape);
+}
+
+int32_t pasa_mask_words(int32_t n_blocks) { return n_blocks < 1 ? PASA_EINVAL : (n_blocks + 31) / 32; }
+
+size_t pasa_score_workspace_bytes(const pasa_shape_t* shape) {
+  if (check_shape(shape) != PASA_OK) return 0;
+  const size_t one = align_up((size_t)shape->B * shape->H * num_blocks(shape) * shape->d * 4);
+  return 2 * one;
+}
+
+size_t pasa_attn_workspace_bytes(const pasa_shape_t* shape) {
+  if (check_shape(shape) != PASA_OK) return 0;
+  if (check_group(shape->group, num_blocks(shape)) != PASA_OK) return 0;
+  const size_t t = carve_attn(shape).total;
+  return t ? t : kAlign;  // never zero for a valid shape, so that 0 always means "bad shape"
+}
+
+int pasa_block_score(const void* q, const void* k, const pasa_shape_t* shape, const float* key_bias, float* scores,
+                     void* ws, size_t ws_bytes, void* stream) {
+  const int rc = check_shape(shape);
+  if (rc != PASA_OK) return rc;
+  if (!q || !k || !scores || !ws) return PASA_EINVAL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(scores) || !aligned16(ws)) return PASA_EALIGN;
+  if (ws_bytes < pasa_score_workspace_bytes(shape)) return PASA_EWORKSPACE;
+  ScoreParams p{};
+  p.q = static_cast<const uint16_t*>(q);
+  p.k = static_cast<const uint16_t*>(k);
+  p.stride_b = shape->stride_b; p.stride_h = shape->stride_h; p.stride_n = shape->stride_n;
+  p.bh = shape->B * shape->H; p.H = shape->H; p.n = shape->n; p.nb = num_blocks(shape);
+  p.block = shape->block; p.d = shape->d;
+  p.scale = effective_scale(shape);
+  p.key_bias = key_bias;
+  p.qbar = static_cast<float*>(ws);
+  p.kbar = reinterpret_cast<float*>(static_cast<char*>(ws) + pasa_score_workspace_bytes(shape) / 2);
+  p.scores = scores;
+  return pasa_launch_block_score(p, static_cast<hipStream_t>(stream)) == hipSuccess ? PASA_OK : PASA_EHIP;
+}
+
+int pasa_route(const float* scores, int32_t BH, int32_t n_blocks, int32_t k_sel, uint64_t seed, float noise_amp,
+               int32_t* idx, uint32_t* mask, void* stream) {
+  if (!scores || !idx || BH < 1 || n_blocks < 1) return PASA_EINVAL;
+  if (k_sel < 1 || k_sel > n_blocks) return PASA_EINVAL;
+  if (!(noise_amp >= 0.f) || isinf(noise_amp)) return PASA_EINVAL;
+  if (n_blocks > kRouteMaxBlocks) return PASA_EUNSUPPORTED;
+  RouteParams p{};
+  p.scores = scores;
+  p.bh = BH; p.nb = n_blocks; p.k_sel = k_sel; p.mask_words = (n_blocks + 31) / 32;
+  p.seed_lo = (uint32_t)(seed & 0xffffffffu); p.seed_hi = (uint32_t)(seed >> 32);
+  p.amp = noise_amp;
+  p.idx = idx; p.mask = mask;
+  return pasa_launch_route(p, static_cast<hipStream_t>(stream)) == hipSuccess ? PASA_OK : PASA_EHIP;
+}
+
+static int attn_common(const void* q, const void* k, const void* v, const pasa_shape_t* shape, const int32_t* idx,
+                       const uint32_t* mask, int32_t k_sel, void* out, float* lse, void* ws, size_t ws_bytes,
+                       void* stream, bool sparse) {
+  const int rc = check_shape(shape);
+  if (rc != PASA_OK) return rc;
+  const int nb = num_blocks(shape);
+  if (!q || !k || !v || !out || !ws) return PASA_EINVAL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(ws)) return PASA_EALIGN;
+  if (out == q || out == k || out == v) return PASA_EINVAL;
+  pasa_shape_t s = *shape;
+  if (!sparse) s.group = 0;
+  if (sparse) {
+    const int rg = check_group(s.group, nb);
+    if (rg != PASA_OK) return rg;
+    if (!idx || k_sel < 1 || k_sel > nb) return PASA_EINVAL;
+    if (s.group > 0 && !mask) return PASA_EINVAL;
+  }
+  if (ws_bytes < pasa_attn_workspace_bytes(&s)) return PASA_EWORKSPACE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const AttnWorkspace w = carve_attn(&s);
+  char* base = static_cast<char*>(ws);
+  const int tail = s.n - (nb - 1) * s.block;
+
+  AttnParams a{};
+  a.q = static_cast<const uint16_t*>(q); a.k = static_cast<const uint16_t*>(k); a.v = static_cast<const uint16_t*>(v);
+  a.o = static_cast<uint16_t*>(out); a.lse = lse;
+  a.stride_b = s.stride_b; a.stride_h = s.stride_h; a.stride_n = s.stride_n;
+  a.bh = s.B * s.H; a.H = s.H; a.n = s.n; a.nb = nb; a.block = s.block; a.tail = tail;
+  a.scale = effective_scale(&s);
+  if (sparse) {
+    a.idx = idx; a.mask = mask; a.k_sel = k_sel; a.mask_words = (nb + 31) / 32;
+    a.group = s.group >= nb ? nb : s.group;
+    if (s.group > 0) {
+      StatsParams t{};
+      t.k = a.k; t.v = a.v;
+      t.stride_b = s.stride_b; t.stride_h = s.stride_h; t.stride_n = s.stride_n;
+      t.bh = a.bh; t.H = s.H; t.n = s.n; t.nb = nb; t.block = s.block; t.tail = tail; t.d = s.d;
+      t.group = a.group; t.n_groups = w.n_groups; t.unit = w.unit; t.n_units = w.n_units;
+      t.scale = a.scale;
+      t.kbar = reinterpret_cast<uint16_t*>(base + w.kbar);
+      t.vs = reinterpret_cast<uint16_t*>(base + w.vs);
+      t.hg = reinterpret_cast<uint16_t*>(base + w.hg);
+      t.partial = reinterpret_cast<float*>(base + w.partial);
+      if (pasa_launch_kv_stats(t, st) != hipSuccess) return PASA_EHIP;
+      a.kbar = t.kbar; a.vs = t.vs; a.hg = t.hg; a.n_groups = w.n_groups;
+    }
+  }
+  return pasa_launch_attn(a, sparse, s.d, st) == hipSuccess ? PASA_OK : PASA_EHIP;
+}
+
+int pasa_sparse_attn_fwd(const void* q, const void* k, const void* v, const pasa_shape_t* shape, const int32_t* idx,
+                         const uint32_t* mask, int32_t k_sel, void* out, float* lse, void* ws, size_t ws_bytes,
+                         void* stream) {
+  return attn_common(q, k, v, shape, idx, mask, k_sel, out, lse, ws, ws_bytes, stream, true);
+}
+
+int pasa_attn_dense_ref(const void* q, const void* k, const void* v, const pasa_shape_t* shape, void* out, float* lse,
+                        void* ws, size_t ws_bytes, void* stream) {
+  return attn_common(q, k, v, shape, nullptr, nullptr, 0, out, lse, ws, ws_bytes, stream, false);
+}
+
+}  // extern "C"

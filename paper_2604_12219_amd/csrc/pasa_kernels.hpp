@@ -1,0 +1,70 @@
+// Host-side launch interface between the C ABI (pasa_api.hip) and the kernel files.
+// Every launcher validates nothing: shapes have been checked by the caller.  Each returns
+// hipGetLastError() after its last launch and never synchronises.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+struct AttnParams {
+  const uint16_t* q;
+  const uint16_t* k;
+  const uint16_t* v;
+  uint16_t* o;
+  float* lse;  // nullable
+  int64_t stride_b, stride_h, stride_n;
+  int32_t bh, H, n, nb, block, tail;  // tail = valid tokens of the last block
+  float scale, c;                     // c = scale * log2(e), filled in by the launcher
+  int32_t q_tiles;                    // filled in by the launcher
+  // sparse path only
+  const int32_t* idx;
+  const uint32_t* mask;
+  int32_t k_sel, mask_words;
+  const uint16_t* kbar;  // bf16 [BH][nb][d]   block-mean keys
+  const uint16_t* vs;    // bf16 [BH][nb][d]   block value sums
+  const uint16_t* hg;    // bf16 [BH][n_groups][d*d] scaled group matrices in MFMA operand order
+  int32_t group, n_groups;
+};
+
+// dense (sparse = false) or piecewise sparse attention; d in {64,128}, block in {64,128}
+hipError_t pasa_launch_attn(AttnParams p, bool sparse, int d, hipStream_t stream);
+
+struct StatsParams {
+  const uint16_t* k;
+  const uint16_t* v;
+  int64_t stride_b, stride_h, stride_n;
+  int32_t bh, H, n, nb, block, tail, d;
+  int32_t group;     // > 0
+  int32_t n_groups;  // ceil(nb / group)
+  int32_t unit;      // blocks summed by one workgroup: min(group, 32)
+  int32_t n_units;   // units per head
+  float scale;
+  uint16_t* kbar;    // out bf16 [BH][nb][d]
+  uint16_t* vs;      // out bf16 [BH][nb][d]
+  float* partial;    // scratch fp32 [BH][n_units][d][d]: sum over the unit's blocks of H_j
+  uint16_t* hg;      // out bf16 [BH][n_groups][d*d], operand order, times scale
+};
+hipError_t pasa_launch_kv_stats(const StatsParams& p, hipStream_t stream);
+
+struct ScoreParams {
+  const uint16_t* q;
+  const uint16_t* k;
+  int64_t stride_b, stride_h, stride_n;
+  int32_t bh, H, n, nb, block, d;
+  float scale;
+  const float* key_bias;  // nullable [BH][nb]
+  float* qbar;            // scratch fp32 [BH][nb][d]
+  float* kbar;            // scratch fp32 [BH][nb][d]
+  float* scores;          // out fp32 [BH][nb][nb]
+};
+hipError_t pasa_launch_block_score(const ScoreParams& p, hipStream_t stream);
+
+struct RouteParams {
+  const float* scores;
+  int32_t bh, nb, k_sel, mask_words;
+  uint32_t seed_lo, seed_hi;
+  float amp;
+  int32_t* idx;
+  uint32_t* mask;  // nullable
+};
+constexpr int kRouteMaxBlocks = 4096;  // keys of 4 rows are staged in 64 KB of LDS
+hipError_t pasa_launch_route(const RouteParams& p, hipStream_t stream);

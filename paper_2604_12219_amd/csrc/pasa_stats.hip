@@ -1,0 +1,160 @@
+// Key/value block statistics of the PASA forward (Eq.4's inner sum, Eq.5, Eq.12) for gfx950.
+//
+//   Kbar_j = mean_n K_{j,n}              -> bf16 [BH][N_B][d]
+//   VS_j   = sum_n  V_{j,n}              -> bf16 [BH][N_B][d]
+//   Hg_g   = mean_{j in group g} H_j,  H_j = sum_n (K_{j,n} - Kbar_j)^T V_{j,n} = K_j^T V_j - Kbar_j^T VS_j
+//
+// H_j is never written to memory.  A workgroup owns a "unit" of consecutive blocks (a whole group
+// when the group has at most 32 blocks, else 32 blocks of it), accumulates sum_j K_j^T V_j on the
+// matrix cores with fp32 accumulators (both operands are fetched from the row-major LDS tiles with
+// transposing LDS reads, the contraction runs over tokens), subtracts the rank-one term of every
+// block in fp32, and writes the unit's sum.  A second small kernel averages the units of a group,
+// applies the logit scale and stores the matrix as bf16 in the order the attention kernel's MFMA
+// consumes it.
+#include "pasa_device.hpp"
+#include "pasa_kernels.hpp"
+
+namespace {
+
+template <int D>
+__global__ void __launch_bounds__(256) kv_stats_kernel(StatsParams p) {
+  constexpr int T = 256;
+  constexpr int TI = D / 64;  // 32x32 result tiles per wave along each of d_in, d_out
+  constexpr int TILE_BYTES = 64 * 2 * D;
+  __shared__ __attribute__((aligned(16))) char smem[2 * TILE_BYTES];
+  __shared__ float kmean_s[D], vsum_s[D];
+  char* const k_lds = smem;
+  char* const v_lds = smem + TILE_BYTES;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5;
+  const int u = blockIdx.x, bh = blockIdx.y;
+  const int64_t head_off = (int64_t)(bh / p.H) * p.stride_b + (int64_t)(bh % p.H) * p.stride_h;
+  const uint16_t* const kb = p.k + head_off;
+  const uint16_t* const vb = p.v + head_off;
+  const int j_lo = u * p.unit, j_hi = min(j_lo + p.unit, p.nb);
+  const int tiles_per_block = p.block / 64;
+
+  f32x16 acc[TI][TI];
+#pragma unroll
+  for (int a = 0; a < TI; ++a)
+#pragma unroll
+    for (int b = 0; b < TI; ++b) acc[a][b] = f32x16{0};
+  const int tin0 = (wave >> 1) * TI, tout0 = (wave & 1) * TI;
+
+  // thread c < D sums column c of K, thread D + c column c of V
+  const bool is_k_col = tid < D, is_v_col = (tid >= D) && (tid < 2 * D);
+  const int col = is_k_col ? tid : tid - D;
+  float colsum = 0.f;
+
+  TileStage<D, T> sk, sv;
+  const int n_tiles = (j_hi - j_lo) * tiles_per_block;
+  auto tile_row0 = [&](int t) { return (j_lo + t / tiles_per_block) * p.block + (t % tiles_per_block) * 64; };
+  sk.load(kb, p.stride_n, tile_row0(0), 64, p.n, tid);
+  sv.load(vb, p.stride_n, tile_row0(0), 64, p.n, tid);
+
+  for (int t = 0; t < n_tiles; ++t) {
+    sk.store(k_lds, 64, tid);
+    sv.store(v_lds, 64, tid);
+    __syncthreads();
+    if (t + 1 < n_tiles) {
+      sk.load(kb, p.stride_n, tile_row0(t + 1), 64, p.n, tid);
+      sv.load(vb, p.stride_n, tile_row0(t + 1), 64, p.n, tid);
+    }
+    if (is_k_col || is_v_col) {
+      const char* src = is_k_col ? k_lds : v_lds;
+#pragma unroll 8
+      for (int r = 0; r < 64; ++r) {
+        const __bf16 x = *reinterpret_cast<const __bf16*>(src + lds_chunk_off<D>(r, col >> 3) + (col & 7) * 2);
+        colsum += (float)x;
+      }
+    }
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      bf16x8 af[TI], bf[TI];
+#pragma unroll
+      for (int a = 0; a < TI; ++a) af[a] = col_frag<D>(k_lds, 16 * ks, 32 * (tin0 + a), lane);
+#pragma unroll
+      for (int b = 0; b < TI; ++b) bf[b] = col_frag<D>(v_lds, 16 * ks, 32 * (tout0 + b), lane);
+#pragma unroll
+      for (int a = 0; a < TI; ++a)
+#pragma unroll
+        for (int b = 0; b < TI; ++b) acc[a][b] = mfma32(af[a], bf[b], acc[a][b]);
+    }
+    const bool block_done = (t % tiles_per_block) == tiles_per_block - 1;
+    if (block_done) {
+      const int j = j_lo + t / tiles_per_block;
+      const int len = (j == p.nb - 1) ? p.tail : p.block;
+      if (is_k_col) {
+        const float mean = colsum / (float)len;
+        kmean_s[col] = mean;
+        p.kbar[((int64_t)bh * p.nb + j) * D + col] = __builtin_bit_cast(uint16_t, (__bf16)mean);
+      } else if (is_v_col) {
+        vsum_s[col] = colsum;
+        p.vs[((int64_t)bh * p.nb + j) * D + col] = __builtin_bit_cast(uint16_t, (__bf16)colsum);
+      }
+      colsum = 0.f;
+    }
+    __syncthreads();  // tiles consumed; block statistics visible
+    if (block_done) {
+#pragma unroll
+      for (int a = 0; a < TI; ++a)
+#pragma unroll
+        for (int b = 0; b < TI; ++b) {
+          const float vcol = vsum_s[32 * (tout0 + b) + (lane & 31)];
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[a][b][r] -= kmean_s[32 * (tin0 + a) + mfma_row(r, h)] * vcol;
+        }
+    }
+  }
+
+  float* out = p.partial + ((int64_t)bh * p.n_units + u) * D * D;
+#pragma unroll
+  for (int a = 0; a < TI; ++a)
+#pragma unroll
+    for (int b = 0; b < TI; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        out[(32 * (tin0 + a) + mfma_row(r, h)) * D + 32 * (tout0 + b) + (lane & 31)] = acc[a][b][r];
+}
+
+// partial [BH][n_units][d_in][d_out] fp32 -> hg [BH][n_groups] in operand order:
+// element ((t*(D/16) + s)*64 + lane)*8 + i  =  scale * Hg[d_in = 16s + 8(lane>>5) + i][d_out = 32t + (lane&31)]
+template <int D>
+__global__ void __launch_bounds__(256) hg_finish_kernel(StatsParams p) {
+  const int g = blockIdx.x, bh = blockIdx.y;
+  int upg = 1;  // units per group
+  if (p.group > 32) upg = (p.group >= p.nb) ? p.n_units : p.group / 32;
+  const int u_lo = g * upg, u_hi = min(u_lo + upg, p.n_units);
+  const int blocks_in_group = min((g + 1) * p.group, p.nb) - g * p.group;
+  const float f = p.scale / (float)blocks_in_group;
+  const float* part = p.partial + (int64_t)bh * p.n_units * D * D;
+  uint16_t* out = p.hg + ((int64_t)bh * p.n_groups + g) * D * D;
+  for (int f8 = threadIdx.x; f8 < D * D / 8; f8 += 256) {  // one 16-byte operand fragment per thread
+    const int l = f8 & 63, ts = f8 >> 6;
+    const int s = ts % (D / 16), t = ts / (D / 16);
+    const int d_out = 32 * t + (l & 31);
+    bf16x8 v;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int d_in = 16 * s + 8 * (l >> 5) + i;
+      float sum = 0.f;
+      for (int u = u_lo; u < u_hi; ++u) sum += part[((int64_t)u * D + d_in) * D + d_out];
+      v[i] = (__bf16)(sum * f);
+    }
+    *reinterpret_cast<bf16x8*>(out + (int64_t)f8 * 8) = v;
+  }
+}
+
+}  // namespace
+
+hipError_t pasa_launch_kv_stats(const StatsParams& p, hipStream_t stream) {
+  dim3 g1(p.n_units, p.bh), g2(p.n_groups, p.bh);
+  if (p.d == 128) {
+    hipLaunchKernelGGL(kv_stats_kernel<128>, g1, dim3(256), 0, stream, p);
+    hipLaunchKernelGGL(hg_finish_kernel<128>, g2, dim3(256), 0, stream, p);
+  } else {
+    hipLaunchKernelGGL(kv_stats_kernel<64>, g1, dim3(256), 0, stream, p);
+    hipLaunchKernelGGL(hg_finish_kernel<64>, g2, dim3(256), 0, stream, p);
+  }
+  return hipGetLastError();
+}

@@ -1,0 +1,217 @@
+"""ctypes binding of the C ABI in ``include/pasa.h``: argument marshalling only.
+
+Tensors are torch tensors on the GPU; the binding passes their device pointers, the current HIP
+stream and sizes straight through.  Every step of the forward runs in the HIP kernels.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libpasa_hip.so")
+_lib = None
+
+EXPORTS = ("pasa_strerror", "pasa_topk_count", "pasa_num_blocks", "pasa_mask_words", "pasa_score_workspace_bytes",
+           "pasa_attn_workspace_bytes", "pasa_block_score", "pasa_route", "pasa_sparse_attn_fwd", "pasa_attn_dense_ref")
+
+
+class PasaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = load_library().pasa_strerror(status).decode()
+        super().__init__(f"{where}: {msg} (status {status})")
+
+
+class _CShape(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("n", ctypes.c_int32), ("d", ctypes.c_int32),
+                ("block", ctypes.c_int32), ("group", ctypes.c_int32),
+                ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_n", ctypes.c_int64),
+                ("scale", ctypes.c_float)]
+
+
+@dataclass
+class Shape:
+    B: int
+    H: int
+    n: int
+    d: int
+    block: int = 64
+    group: int = 32
+    stride_b: int = 0
+    stride_h: int = 0
+    stride_n: int = 0
+    scale: float = 0.0
+
+    @staticmethod
+    def of(x: torch.Tensor, block: int = 64, group: int = 32, scale: float = 0.0) -> "Shape":
+        if x.dim() != 4 or x.stride(3) != 1:
+            raise ValueError("expected a [B, H, n, d] tensor with contiguous last dimension")
+        B, H, n, d = x.shape
+        return Shape(B, H, n, d, block, group, x.stride(0), x.stride(1), x.stride(2), scale)
+
+    def c(self) -> _CShape:
+        return _CShape(self.B, self.H, self.n, self.d, self.block, self.group, self.stride_b, self.stride_h,
+                       self.stride_n, self.scale)
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libpasa_hip.so; raises if it has not been built (there is no fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python -m paper_2604_12219_amd.build` "
+                               "(hipcc, gfx950). There is no CPU fallback.")
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, sp = ctypes.c_void_p, ctypes.POINTER(_CShape)
+        L.pasa_strerror.restype = ctypes.c_char_p
+        L.pasa_strerror.argtypes = [ctypes.c_int]
+        L.pasa_topk_count.restype = ctypes.c_int32
+        L.pasa_topk_count.argtypes = [ctypes.c_int32, ctypes.c_double]
+        L.pasa_num_blocks.restype = ctypes.c_int32
+        L.pasa_num_blocks.argtypes = [sp]
+        L.pasa_mask_words.restype = ctypes.c_int32
+        L.pasa_mask_words.argtypes = [ctypes.c_int32]
+        L.pasa_score_workspace_bytes.restype = ctypes.c_size_t
+        L.pasa_score_workspace_bytes.argtypes = [sp]
+        L.pasa_attn_workspace_bytes.restype = ctypes.c_size_t
+        L.pasa_attn_workspace_bytes.argtypes = [sp]
+        L.pasa_block_score.restype = ctypes.c_int
+        L.pasa_block_score.argtypes = [vp, vp, sp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.pasa_route.restype = ctypes.c_int
+        L.pasa_route.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_uint64, ctypes.c_float,
+                                 vp, vp, vp]
+        L.pasa_sparse_attn_fwd.restype = ctypes.c_int
+        L.pasa_sparse_attn_fwd.argtypes = [vp, vp, vp, sp, vp, vp, ctypes.c_int32, vp, vp, vp, ctypes.c_size_t, vp]
+        L.pasa_attn_dense_ref.restype = ctypes.c_int
+        L.pasa_attn_dense_ref.argtypes = [vp, vp, vp, sp, vp, vp, vp, ctypes.c_size_t, vp]
+        _lib = L
+    return _lib
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise PasaError(rc, where)
+
+
+def topk_count(n_blocks: int, keep_ratio: float) -> int:
+    k = load_library().pasa_topk_count(n_blocks, keep_ratio)
+    if k < 0:
+        raise PasaError(k, "pasa_topk_count")
+    return k
+
+
+def num_blocks(shape: Shape) -> int:
+    nb = load_library().pasa_num_blocks(ctypes.byref(shape.c()))
+    if nb < 0:
+        raise PasaError(nb, "pasa_num_blocks")
+    return nb
+
+
+def mask_words(n_blocks: int) -> int:
+    return load_library().pasa_mask_words(n_blocks)
+
+
+def score_workspace_bytes(shape: Shape) -> int:
+    return load_library().pasa_score_workspace_bytes(ctypes.byref(shape.c()))
+
+
+def attn_workspace_bytes(shape: Shape) -> int:
+    return load_library().pasa_attn_workspace_bytes(ctypes.byref(shape.c()))
+
+
+def _workspace(nbytes: int, device, ws):
+    if ws is None:
+        ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+    return ws
+
+
+def block_score(q, k, shape: Shape, key_bias=None, scores=None, ws=None):
+    """-> scores fp32 [B*H, N_B, N_B]"""
+    L = load_library()
+    nb = num_blocks(shape)
+    if scores is None:
+        scores = torch.empty((shape.B * shape.H, nb, nb), dtype=torch.float32, device=q.device)
+    ws = _workspace(score_workspace_bytes(shape), q.device, ws)
+    _check(L.pasa_block_score(_ptr(q), _ptr(k), ctypes.byref(shape.c()), _ptr(key_bias), _ptr(scores), _ptr(ws),
+                              ws.numel(), _stream()), "pasa_block_score")
+    return scores
+
+
+def route(scores, k_sel: int, seed: int, noise_amp: float, idx=None, mask=None, want_mask: bool = True):
+    """-> (idx int32 [BH, N_B, k_sel] ascending, mask int32-typed bitmap [BH, N_B, ceil(N_B/32)] or None)"""
+    L = load_library()
+    BH, nb, _ = scores.shape
+    if idx is None:
+        idx = torch.empty((BH, nb, max(k_sel, 1)), dtype=torch.int32, device=scores.device)
+    if mask is None and want_mask:
+        mask = torch.empty((BH, nb, (nb + 31) // 32), dtype=torch.int32, device=scores.device)
+    _check(L.pasa_route(_ptr(scores), BH, nb, k_sel, seed & (2**64 - 1), noise_amp, _ptr(idx), _ptr(mask), _stream()),
+           "pasa_route")
+    return idx, mask
+
+
+def sparse_attn_fwd(q, k, v, shape: Shape, idx, mask, out=None, lse=None, ws=None, want_lse: bool = False):
+    L = load_library()
+    if out is None:
+        out = torch.empty_like(q)
+    if lse is None and want_lse:
+        lse = torch.empty((shape.B * shape.H, shape.n), dtype=torch.float32, device=q.device)
+    ws = _workspace(attn_workspace_bytes(shape), q.device, ws)
+    _check(L.pasa_sparse_attn_fwd(_ptr(q), _ptr(k), _ptr(v), ctypes.byref(shape.c()), _ptr(idx), _ptr(mask),
+                                  idx.shape[-1], _ptr(out), _ptr(lse), _ptr(ws), ws.numel(), _stream()),
+           "pasa_sparse_attn_fwd")
+    return (out, lse) if want_lse else out
+
+
+def attn_dense_ref(q, k, v, shape: Shape, out=None, lse=None, ws=None, want_lse: bool = False):
+    L = load_library()
+    if out is None:
+        out = torch.empty_like(q)
+    if lse is None and want_lse:
+        lse = torch.empty((shape.B * shape.H, shape.n), dtype=torch.float32, device=q.device)
+    ws = _workspace(attn_workspace_bytes(shape), q.device, ws)
+    _check(L.pasa_attn_dense_ref(_ptr(q), _ptr(k), _ptr(v), ctypes.byref(shape.c()), _ptr(out), _ptr(lse), _ptr(ws),
+                                 ws.numel(), _stream()), "pasa_attn_dense_ref")
+    return (out, lse) if want_lse else out
+
+
+def forward(q, k, v, keep_ratio: float, seed: int, noise_amp: float, block: int = 64, group: int = 32,
+            scale: float = 0.0, buffers: dict | None = None):
+    """The whole hot path: score -> route -> statistics + piecewise attention. Returns (out, idx).
+
+    ``buffers`` (optional dict) caches every intermediate and workspace between calls.
+    """
+    shape = Shape.of(q, block=block, group=group, scale=scale)
+    nb = num_blocks(shape)
+    k_sel = topk_count(nb, keep_ratio)
+    b = buffers if buffers is not None else {}
+    key = (tuple(q.shape), block, group, k_sel)
+    if b.get("key") != key:
+        b.clear()
+        b["key"] = key
+        b["scores"] = torch.empty((shape.B * shape.H, nb, nb), dtype=torch.float32, device=q.device)
+        b["idx"] = torch.empty((shape.B * shape.H, nb, k_sel), dtype=torch.int32, device=q.device)
+        b["mask"] = torch.empty((shape.B * shape.H, nb, (nb + 31) // 32), dtype=torch.int32, device=q.device)
+        b["ws_score"] = torch.empty(score_workspace_bytes(shape), dtype=torch.uint8, device=q.device)
+        b["ws_attn"] = torch.empty(attn_workspace_bytes(shape), dtype=torch.uint8, device=q.device)
+        b["out"] = torch.empty_like(q)
+    block_score(q, k, shape, scores=b["scores"], ws=b["ws_score"])
+    route(b["scores"], k_sel, seed, noise_amp, idx=b["idx"], mask=b["mask"])
+    sparse_attn_fwd(q, k, v, shape, b["idx"], b["mask"], out=b["out"], ws=b["ws_attn"])
+    return b["out"], b["idx"]

@@ -1,0 +1,190 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle, element by element,
+on the same seeded inputs.  Sizes span several tiles and ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from _util import assert_close, to_f64
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def P():
+    import paper_2604_12219_amd as P
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    P.load_library()
+    return P
+
+
+def _inputs(grid, heads, d, seed=0, batch=1):
+    return workloads.make_qkv(grid, heads, d, seed=seed, device="cuda", batch=batch)
+
+
+# ------------------------------------------------------------------------------------------------
+# dense reference kernel (Eq.1)
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("grid,heads,d", [((4, 16, 16), 2, 64), ((3, 11, 13), 2, 128), ((1, 5, 7), 1, 128),
+                                          ((2, 16, 16), 3, 128)])
+def test_dense_matches_oracle(P, grid, heads, d):
+    q, k, v = _inputs(grid, heads, d)
+    shape = P.Shape.of(q)
+    out, lse = P.attn_dense_ref(q, k, v, shape, want_lse=True)
+    torch.cuda.synchronize()
+    ref, ref_lse = oracle.dense_attention(to_f64(q), to_f64(k), to_f64(v), return_lse=True)
+    assert_close(to_f64(out), ref, what=f"dense {grid} d={d}")
+    np.testing.assert_allclose(lse.cpu().numpy(), ref_lse, atol=2e-2)
+
+
+def test_dense_respects_strides_and_scale(P):
+    q, k, v = _inputs((2, 9, 10), 2, 128)
+    B, H, n, d = q.shape
+    big = torch.zeros((3, B, n, H, d + 8), dtype=torch.bfloat16, device="cuda")  # [which, B, n, H, d+pad]
+    for i, t in enumerate((q, k, v)):
+        big[i, :, :, :, :d] = t.permute(0, 2, 1, 3)
+    qs, ks, vs = (big[i, :, :, :, :d].permute(0, 2, 1, 3) for i in range(3))  # [B,H,n,d] views, n-stride H*(d+8)
+    shape = P.Shape.of(qs, scale=0.11)
+    out = torch.zeros_like(big[0])[:, :, :, :d].permute(0, 2, 1, 3)
+    P.attn_dense_ref(qs, ks, vs, shape, out=out)
+    torch.cuda.synchronize()
+    ref = oracle.dense_attention(to_f64(q), to_f64(k), to_f64(v), scale=0.11)
+    assert_close(to_f64(out), ref, what="strided dense")
+
+
+# ------------------------------------------------------------------------------------------------
+# stage 1: scores
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("grid,d,block", [((4, 16, 16), 64, 64), ((3, 21, 13), 128, 64), ((3, 21, 13), 128, 128)])
+def test_block_scores_match_oracle(P, grid, d, block):
+    q, k, _ = _inputs(grid, 2, d)
+    shape = P.Shape.of(q, block=block)
+    nb = P.num_blocks(shape)
+    bias = torch.randn((2, nb), device="cuda", generator=torch.Generator("cuda").manual_seed(1))
+    s0 = P.block_score(q, k, shape)
+    s1 = P.block_score(q, k, shape, key_bias=bias)
+    torch.cuda.synchronize()
+    ref = oracle.block_scores(to_f64(q), to_f64(k), block)
+    tol = 1e-3 * np.abs(ref).max()
+    np.testing.assert_allclose(s0.cpu().numpy(), ref, atol=tol, rtol=0)
+    np.testing.assert_allclose(s1.cpu().numpy(), ref + bias.cpu().numpy()[:, None, :], atol=tol, rtol=0)
+
+
+# ------------------------------------------------------------------------------------------------
+# stage 2: routing is bit-exact against the oracle fed the GPU's scores
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("nb,k_sel,amp", [(16, 4, 0.0), (16, 4, 0.5), (67, 9, 1.0), (130, 130, 0.3), (515, 77, 2.0),
+                                          (1182, 177, 0.7), (64, 1, 0.1)])
+def test_routing_bit_exact(P, nb, k_sel, amp):
+    g = torch.Generator("cuda").manual_seed(nb)
+    scores = torch.randn((3, nb, nb), device="cuda", generator=g)
+    scores[0, 0, : nb // 2] = 0.25  # ties
+    scores[1, 1, :] = -1.5          # a fully tied row
+    scores[2, 0, 0] = -0.0
+    seed = 0x1234_5678_9ABC_DEF0 + nb
+    idx, mask = P.route(scores, k_sel, seed, amp)
+    torch.cuda.synchronize()
+    want = oracle.route(scores.cpu().numpy(), k_sel, seed, amp)
+    np.testing.assert_array_equal(idx.cpu().numpy(), want)
+    words = mask.cpu().numpy().view(np.uint32)
+    bits = np.zeros((3, nb, words.shape[-1] * 32), bool)
+    for h in range(3):
+        for i in range(nb):
+            bits[h, i, want[h, i]] = True
+    packed = np.packbits(bits.reshape(3, nb, -1, 32), axis=-1, bitorder="little").view(np.uint32)[..., 0]
+    np.testing.assert_array_equal(words, packed)
+
+
+def test_routing_on_real_scores_and_determinism(P):
+    q, k, _ = _inputs((4, 16, 16), 2, 64)
+    shape = P.Shape.of(q)
+    scores = P.block_score(q, k, shape)
+    idx, mask = P.route(scores, 4, 99, 0.4)
+    idx2, mask2 = P.route(scores, 4, 99, 0.4)
+    idx3, _ = P.route(scores, 4, 100, 0.4)
+    torch.cuda.synchronize()
+    assert torch.equal(idx, idx2) and torch.equal(mask, mask2)
+    assert not torch.equal(idx, idx3)
+    np.testing.assert_array_equal(idx.cpu().numpy(), oracle.route(scores.cpu().numpy(), 4, 99, 0.4))
+
+
+# ------------------------------------------------------------------------------------------------
+# stages 3+4: piecewise attention
+# ------------------------------------------------------------------------------------------------
+def _run_sparse(P, q, k, v, block, group, keep, seed=3, amp=0.3):
+    shape = P.Shape.of(q, block=block, group=group)
+    nb = P.num_blocks(shape)
+    k_sel = P.topk_count(nb, keep)
+    scores = P.block_score(q, k, shape)
+    idx, mask = P.route(scores, k_sel, seed, amp)
+    out, lse = P.sparse_attn_fwd(q, k, v, shape, idx, mask, want_lse=True)
+    torch.cuda.synchronize()
+    return out, lse, idx
+
+
+CASES = [
+    # grid, heads, d, block, group, keep
+    ((4, 16, 16), 2, 64, 64, 32, 0.25),     # the tiny workload
+    ((4, 16, 16), 2, 128, 64, 32, 0.25),
+    ((5, 21, 13), 2, 128, 64, 32, 0.2),     # n=1365: 22 blocks, tail of 21 tokens
+    ((9, 20, 23), 1, 128, 64, 32, 0.15),    # n=4140: 65 blocks (3 chunks, last group 1 block), tail 44
+    ((9, 20, 23), 1, 128, 128, 32, 0.1),    # block 128: 33 blocks, tail 44 (< 64: second half-tile empty)
+    ((9, 20, 23), 1, 128, 64, 0, 0.15),     # approximation off
+    ((9, 20, 23), 1, 128, 64, 1000, 0.15),  # one global matrix (Eq.6/Eq.7)
+    ((9, 20, 23), 1, 128, 64, 64, 0.15),    # 64 blocks per group
+    ((9, 20, 23), 1, 128, 64, 8, 0.15),     # small groups
+    ((9, 20, 23), 1, 128, 64, 1, 0.05),     # per-block first-order term (Eq.13)
+    ((9, 20, 23), 1, 64, 128, 32, 0.1),
+]
+
+
+@pytest.mark.parametrize("grid,heads,d,block,group,keep", CASES)
+def test_sparse_matches_oracle(P, grid, heads, d, block, group, keep):
+    q, k, v = _inputs(grid, heads, d, seed=7)
+    out, lse, idx = _run_sparse(P, q, k, v, block, group, keep)
+    res = oracle.pasa_attention(to_f64(q), to_f64(k), to_f64(v), idx.cpu().numpy(), block, group=group,
+                                return_all=True)
+    assert_close(to_f64(out), res["o"], what=f"sparse {grid} d={d} b={block} G={group}")
+    np.testing.assert_allclose(lse.cpu().numpy(), res["lse"], atol=2e-2)
+
+
+def test_keep_everything_equals_dense_kernel_and_oracle(P):
+    q, k, v = _inputs((5, 21, 13), 2, 128, seed=2)
+    out, _, idx = _run_sparse(P, q, k, v, 64, 32, 1.0)
+    assert idx.shape[-1] == 22
+    ref = oracle.dense_attention(to_f64(q), to_f64(k), to_f64(v))
+    assert_close(to_f64(out), ref, what="keep=1")
+    dense = P.attn_dense_ref(q, k, v, P.Shape.of(q))
+    torch.cuda.synchronize()
+    assert_close(to_f64(out), to_f64(dense).astype(np.float64), what="keep=1 vs dense kernel")
+
+
+def test_batch_and_heads_are_independent_and_results_are_deterministic(P):
+    q, k, v = _inputs((3, 16, 16), 3, 128, seed=11, batch=2)
+    out, _, idx = _run_sparse(P, q, k, v, 64, 32, 0.25)
+    out2, _, idx2 = _run_sparse(P, q, k, v, 64, 32, 0.25)
+    assert torch.equal(out, out2) and torch.equal(idx, idx2)  # bitwise run-to-run
+    # batch 1, head 2 alone (routing noise is keyed by bh, so feed the same routing rows)
+    shape1 = P.Shape.of(q[1:2, 2:3], block=64, group=32)
+    bh = 1 * 3 + 2
+    nb = idx.shape[1]
+    mask = torch.zeros((1, nb, (nb + 31) // 32), dtype=torch.int32, device="cuda")
+    words = np.zeros((nb, (nb + 31) // 32), np.uint32)
+    for i, row in enumerate(idx[bh].cpu().numpy()):
+        for j in row:
+            words[i, j >> 5] |= np.uint32(1) << np.uint32(j & 31)
+    mask[0] = torch.from_numpy(words.view(np.int32)).cuda()
+    single = P.sparse_attn_fwd(q[1:2, 2:3], k[1:2, 2:3], v[1:2, 2:3], shape1, idx[bh:bh + 1].contiguous(), mask)
+    torch.cuda.synchronize()
+    assert torch.equal(single[0, 0], out[1, 2])
+    ref = oracle.pasa_attention(to_f64(q), to_f64(k), to_f64(v), idx.cpu().numpy(), 64, group=32)
+    assert_close(to_f64(out), ref, what="batch=2")
+
+
+def test_forward_convenience_wrapper(P):
+    q, k, v = _inputs((4, 16, 16), 2, 64)
+    out, idx = P.forward(q, k, v, keep_ratio=0.25, seed=5, noise_amp=0.2)
+    torch.cuda.synchronize()
+    ref = oracle.pasa_attention(to_f64(q), to_f64(k), to_f64(v), idx.cpu().numpy(), 64, group=32)
+    assert_close(to_f64(out), ref, what="forward()")
