@@ -114,6 +114,18 @@ PASA_API int pasa_route(const float* scores, int32_t BH, int32_t n_blocks, int32
                float noise_amp, int32_t* idx, uint32_t* mask, void* stream);
 
 /*
+ * Key/value block statistics (Eq.4's inner sum, Eq.5, Eq.12) -- the query-independent part of
+ * stages 3 and 4, exported on its own so that it can be timed and reused:
+ *   Kbar_j = mean_n K_{j,n},  VS_j = sum_n V_{j,n},
+ *   Hg_g   = mean over the blocks j of group g of  H_j = sum_n (K_{j,n} - Kbar_j)^T V_{j,n}
+ * written into `ws` in the library's internal layout (bf16; Hg pre-multiplied by the logit scale).
+ *   k, v  bf16 [B,H,n,d] (shape strides);  ws scratch of pasa_attn_workspace_bytes(shape) bytes,
+ *   256-byte aligned.  shape->group == 0 is accepted and does nothing.
+ */
+PASA_API int pasa_kv_stats(const void* k, const void* v, const pasa_shape_t* shape, void* ws, size_t ws_bytes,
+                           void* stream);
+
+/*
  * Stages 3 and 4 -- piecewise attention (Eq.7 with the grouped first-order term of Eq.14).
  * For query token t of query block i, q~ = Q_t * scale, S = idx[bh, i, :], U = the other blocks:
  *   Num = sum_{j in S} sum_{n < b_j} exp(q~ K_{j,n}) V_{j,n}
@@ -121,8 +133,9 @@ PASA_API int pasa_route(const float* scores, int32_t BH, int32_t n_blocks, int32
  *       + sum_g (sum_{j in U and in group g} a_j) (q~ Hg_g)                                  (Eq.14)
  *   Den = sum_{j in S} sum_{n < b_j} exp(q~ K_{j,n}) + sum_{j in U} b_j a_j
  *   O_t = Num / Den   (one online-softmax normaliser; b_j = valid tokens of block j)
- * with Hg_g the mean over the blocks of group g of H_j = sum_n (K_{j,n} - Kbar_j)^T V_{j,n}
- * (Eq.5, Eq.12).  The key/value statistics are recomputed by every call (they depend on K and V only).
+ * pasa_sparse_attn_fwd recomputes the key/value statistics on every call (pasa_kv_stats, then the
+ * attention kernel).  pasa_sparse_attn_fwd_prepared runs the attention kernel alone and requires
+ * that `ws` was filled by pasa_kv_stats for the same k, v and shape and not touched since.
  *   idx    int32 [BH, N_B, k_sel], each row strictly ascending, values in [0, N_B) (not checked)
  *   mask   the bitmap pasa_route wrote for the same idx (required unless shape->group == 0)
  *   out    bf16 [B,H,n,d] (shape strides)
@@ -130,8 +143,11 @@ PASA_API int pasa_route(const float* scores, int32_t BH, int32_t n_blocks, int32
  *   ws     scratch of pasa_attn_workspace_bytes(shape) bytes, 256-byte aligned
  */
 PASA_API int pasa_sparse_attn_fwd(const void* q, const void* k, const void* v, const pasa_shape_t* shape,
-                         const int32_t* idx, const uint32_t* mask, int32_t k_sel, void* out,
-                         float* lse, void* ws, size_t ws_bytes, void* stream);
+                                  const int32_t* idx, const uint32_t* mask, int32_t k_sel, void* out,
+                                  float* lse, void* ws, size_t ws_bytes, void* stream);
+PASA_API int pasa_sparse_attn_fwd_prepared(const void* q, const void* k, const void* v, const pasa_shape_t* shape,
+                                           const int32_t* idx, const uint32_t* mask, int32_t k_sel, void* out,
+                                           float* lse, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Dense attention, Eq.1: O = softmax(Q K^T * scale) V, same kernels with every block selected.

@@ -139,65 +139,95 @@ int pasa_route(const float* scores, int32_t BH, int32_t n_blocks, int32_t k_sel,
   return pasa_launch_route(p, static_cast<hipStream_t>(stream)) == hipSuccess ? PASA_OK : PASA_EHIP;
 }
 
-static int attn_common(const void* q, const void* k, const void* v, const pasa_shape_t* shape, const int32_t* idx,
-                       const uint32_t* mask, int32_t k_sel, void* out, float* lse, void* ws, size_t ws_bytes,
-                       void* stream, bool sparse) {
+// validation shared by the statistics and attention entry points; fills `s` (group normalised)
+static int check_attn_args(const pasa_shape_t* shape, bool sparse, const void* ws, size_t ws_bytes, pasa_shape_t* s) {
   const int rc = check_shape(shape);
   if (rc != PASA_OK) return rc;
-  const int nb = num_blocks(shape);
-  if (!q || !k || !v || !out || !ws) return PASA_EINVAL;
-  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out) || !aligned16(ws)) return PASA_EALIGN;
+  *s = *shape;
+  if (!sparse) s->group = 0;
+  const int rg = check_group(s->group, num_blocks(s));
+  if (rg != PASA_OK) return rg;
+  if (!ws) return PASA_EINVAL;
+  if (!aligned16(ws)) return PASA_EALIGN;
+  if (ws_bytes < pasa_attn_workspace_bytes(s)) return PASA_EWORKSPACE;
+  return PASA_OK;
+}
+
+int pasa_kv_stats(const void* k, const void* v, const pasa_shape_t* shape, void* ws, size_t ws_bytes, void* stream) {
+  pasa_shape_t s;
+  const int rc = check_attn_args(shape, true, ws, ws_bytes, &s);
+  if (rc != PASA_OK) return rc;
+  if (!k || !v) return PASA_EINVAL;
+  if (!aligned16(k) || !aligned16(v)) return PASA_EALIGN;
+  if (s.group == 0) return PASA_OK;
+  const int nb = num_blocks(&s);
+  const AttnWorkspace w = carve_attn(&s);
+  char* base = static_cast<char*>(ws);
+  StatsParams t{};
+  t.k = static_cast<const uint16_t*>(k); t.v = static_cast<const uint16_t*>(v);
+  t.stride_b = s.stride_b; t.stride_h = s.stride_h; t.stride_n = s.stride_n;
+  t.bh = s.B * s.H; t.H = s.H; t.n = s.n; t.nb = nb; t.block = s.block; t.tail = s.n - (nb - 1) * s.block; t.d = s.d;
+  t.group = s.group >= nb ? nb : s.group; t.n_groups = w.n_groups; t.unit = w.unit; t.n_units = w.n_units;
+  t.scale = effective_scale(&s);
+  t.kbar = reinterpret_cast<uint16_t*>(base + w.kbar);
+  t.vs = reinterpret_cast<uint16_t*>(base + w.vs);
+  t.hg = reinterpret_cast<uint16_t*>(base + w.hg);
+  t.partial = reinterpret_cast<float*>(base + w.partial);
+  return pasa_launch_kv_stats(t, static_cast<hipStream_t>(stream)) == hipSuccess ? PASA_OK : PASA_EHIP;
+}
+
+static int attn_common(const void* q, const void* k, const void* v, const pasa_shape_t* shape, const int32_t* idx,
+                       const uint32_t* mask, int32_t k_sel, void* out, float* lse, void* ws, size_t ws_bytes,
+                       void* stream, bool sparse, bool with_stats) {
+  pasa_shape_t s;
+  const int rc = check_attn_args(shape, sparse, ws, ws_bytes, &s);
+  if (rc != PASA_OK) return rc;
+  const int nb = num_blocks(&s);
+  if (!q || !k || !v || !out) return PASA_EINVAL;
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return PASA_EALIGN;
   if (out == q || out == k || out == v) return PASA_EINVAL;
-  pasa_shape_t s = *shape;
-  if (!sparse) s.group = 0;
   if (sparse) {
-    const int rg = check_group(s.group, nb);
-    if (rg != PASA_OK) return rg;
     if (!idx || k_sel < 1 || k_sel > nb) return PASA_EINVAL;
     if (s.group > 0 && !mask) return PASA_EINVAL;
   }
-  if (ws_bytes < pasa_attn_workspace_bytes(&s)) return PASA_EWORKSPACE;
-  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (sparse && with_stats) {
+    const int rs = pasa_kv_stats(k, v, &s, ws, ws_bytes, stream);
+    if (rs != PASA_OK) return rs;
+  }
   const AttnWorkspace w = carve_attn(&s);
   char* base = static_cast<char*>(ws);
-  const int tail = s.n - (nb - 1) * s.block;
-
   AttnParams a{};
   a.q = static_cast<const uint16_t*>(q); a.k = static_cast<const uint16_t*>(k); a.v = static_cast<const uint16_t*>(v);
   a.o = static_cast<uint16_t*>(out); a.lse = lse;
   a.stride_b = s.stride_b; a.stride_h = s.stride_h; a.stride_n = s.stride_n;
-  a.bh = s.B * s.H; a.H = s.H; a.n = s.n; a.nb = nb; a.block = s.block; a.tail = tail;
+  a.bh = s.B * s.H; a.H = s.H; a.n = s.n; a.nb = nb; a.block = s.block; a.tail = s.n - (nb - 1) * s.block;
   a.scale = effective_scale(&s);
   if (sparse) {
     a.idx = idx; a.mask = mask; a.k_sel = k_sel; a.mask_words = (nb + 31) / 32;
     a.group = s.group >= nb ? nb : s.group;
-    if (s.group > 0) {
-      StatsParams t{};
-      t.k = a.k; t.v = a.v;
-      t.stride_b = s.stride_b; t.stride_h = s.stride_h; t.stride_n = s.stride_n;
-      t.bh = a.bh; t.H = s.H; t.n = s.n; t.nb = nb; t.block = s.block; t.tail = tail; t.d = s.d;
-      t.group = a.group; t.n_groups = w.n_groups; t.unit = w.unit; t.n_units = w.n_units;
-      t.scale = a.scale;
-      t.kbar = reinterpret_cast<uint16_t*>(base + w.kbar);
-      t.vs = reinterpret_cast<uint16_t*>(base + w.vs);
-      t.hg = reinterpret_cast<uint16_t*>(base + w.hg);
-      t.partial = reinterpret_cast<float*>(base + w.partial);
-      if (pasa_launch_kv_stats(t, st) != hipSuccess) return PASA_EHIP;
-      a.kbar = t.kbar; a.vs = t.vs; a.hg = t.hg; a.n_groups = w.n_groups;
-    }
+    a.kbar = reinterpret_cast<const uint16_t*>(base + w.kbar);
+    a.vs = reinterpret_cast<const uint16_t*>(base + w.vs);
+    a.hg = reinterpret_cast<const uint16_t*>(base + w.hg);
+    a.n_groups = w.n_groups;
   }
-  return pasa_launch_attn(a, sparse, s.d, st) == hipSuccess ? PASA_OK : PASA_EHIP;
+  return pasa_launch_attn(a, sparse, s.d, static_cast<hipStream_t>(stream)) == hipSuccess ? PASA_OK : PASA_EHIP;
 }
 
 int pasa_sparse_attn_fwd(const void* q, const void* k, const void* v, const pasa_shape_t* shape, const int32_t* idx,
                          const uint32_t* mask, int32_t k_sel, void* out, float* lse, void* ws, size_t ws_bytes,
                          void* stream) {
-  return attn_common(q, k, v, shape, idx, mask, k_sel, out, lse, ws, ws_bytes, stream, true);
+  return attn_common(q, k, v, shape, idx, mask, k_sel, out, lse, ws, ws_bytes, stream, true, true);
+}
+
+int pasa_sparse_attn_fwd_prepared(const void* q, const void* k, const void* v, const pasa_shape_t* shape,
+                                  const int32_t* idx, const uint32_t* mask, int32_t k_sel, void* out, float* lse,
+                                  void* ws, size_t ws_bytes, void* stream) {
+  return attn_common(q, k, v, shape, idx, mask, k_sel, out, lse, ws, ws_bytes, stream, true, false);
 }
 
 int pasa_attn_dense_ref(const void* q, const void* k, const void* v, const pasa_shape_t* shape, void* out, float* lse,
                         void* ws, size_t ws_bytes, void* stream) {
-  return attn_common(q, k, v, shape, nullptr, nullptr, 0, out, lse, ws, ws_bytes, stream, false);
+  return attn_common(q, k, v, shape, nullptr, nullptr, 0, out, lse, ws, ws_bytes, stream, false, false);
 }
 
 }  // extern "C"

@@ -16,7 +16,8 @@ _LIB_PATH = os.path.join(_HERE, "libpasa_hip.so")
 _lib = None
 
 EXPORTS = ("pasa_strerror", "pasa_topk_count", "pasa_num_blocks", "pasa_mask_words", "pasa_score_workspace_bytes",
-           "pasa_attn_workspace_bytes", "pasa_block_score", "pasa_route", "pasa_sparse_attn_fwd", "pasa_attn_dense_ref")
+           "pasa_attn_workspace_bytes", "pasa_block_score", "pasa_route", "pasa_kv_stats", "pasa_sparse_attn_fwd",
+           "pasa_sparse_attn_fwd_prepared", "pasa_attn_dense_ref")
 
 
 class PasaError(RuntimeError):
@@ -90,6 +91,10 @@ def load_library() -> ctypes.CDLL:
                                  vp, vp, vp]
         L.pasa_sparse_attn_fwd.restype = ctypes.c_int
         L.pasa_sparse_attn_fwd.argtypes = [vp, vp, vp, sp, vp, vp, ctypes.c_int32, vp, vp, vp, ctypes.c_size_t, vp]
+        L.pasa_sparse_attn_fwd_prepared.restype = ctypes.c_int
+        L.pasa_sparse_attn_fwd_prepared.argtypes = L.pasa_sparse_attn_fwd.argtypes
+        L.pasa_kv_stats.restype = ctypes.c_int
+        L.pasa_kv_stats.argtypes = [vp, vp, sp, vp, ctypes.c_size_t, vp]
         L.pasa_attn_dense_ref.restype = ctypes.c_int
         L.pasa_attn_dense_ref.argtypes = [vp, vp, vp, sp, vp, vp, vp, ctypes.c_size_t, vp]
         _lib = L
@@ -166,16 +171,28 @@ def route(scores, k_sel: int, seed: int, noise_amp: float, idx=None, mask=None, 
     return idx, mask
 
 
-def sparse_attn_fwd(q, k, v, shape: Shape, idx, mask, out=None, lse=None, ws=None, want_lse: bool = False):
+def kv_stats(k, v, shape: Shape, ws=None):
+    """fills (and returns) the attention workspace with the key/value block statistics"""
     L = load_library()
+    ws = _workspace(attn_workspace_bytes(shape), k.device, ws)
+    _check(L.pasa_kv_stats(_ptr(k), _ptr(v), ctypes.byref(shape.c()), _ptr(ws), ws.numel(), _stream()), "pasa_kv_stats")
+    return ws
+
+
+def sparse_attn_fwd(q, k, v, shape: Shape, idx, mask, out=None, lse=None, ws=None, want_lse: bool = False,
+                    prepared: bool = False):
+    """prepared=True: ``ws`` already holds kv_stats() of the same k, v, shape; run the attention kernel alone"""
+    L = load_library()
+    if prepared and ws is None:
+        raise ValueError("prepared=True needs the workspace kv_stats() filled")
     if out is None:
         out = torch.empty_like(q)
     if lse is None and want_lse:
         lse = torch.empty((shape.B * shape.H, shape.n), dtype=torch.float32, device=q.device)
     ws = _workspace(attn_workspace_bytes(shape), q.device, ws)
-    _check(L.pasa_sparse_attn_fwd(_ptr(q), _ptr(k), _ptr(v), ctypes.byref(shape.c()), _ptr(idx), _ptr(mask),
-                                  idx.shape[-1], _ptr(out), _ptr(lse), _ptr(ws), ws.numel(), _stream()),
-           "pasa_sparse_attn_fwd")
+    fn = L.pasa_sparse_attn_fwd_prepared if prepared else L.pasa_sparse_attn_fwd
+    _check(fn(_ptr(q), _ptr(k), _ptr(v), ctypes.byref(shape.c()), _ptr(idx), _ptr(mask), idx.shape[-1], _ptr(out),
+              _ptr(lse), _ptr(ws), ws.numel(), _stream()), "pasa_sparse_attn_fwd")
     return (out, lse) if want_lse else out
 
 
