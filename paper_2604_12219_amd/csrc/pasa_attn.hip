@@ -156,7 +156,7 @@ PASA_DEVICE void first_order(const uint16_t* hg, WaveState<D>& w, float A, int l
 }
 
 template <int D, int NW, bool SPARSE>
-__global__ void __launch_bounds__(NW * 64) attn_kernel(AttnParams p) {
+__global__ void __launch_bounds__(NW * 64, 2) attn_kernel(AttnParams p) {
   constexpr int T = NW * 64;
   constexpr int TILE_BYTES = 64 * 2 * D;
   __shared__ __attribute__((aligned(16))) char smem[2 * TILE_BYTES];
