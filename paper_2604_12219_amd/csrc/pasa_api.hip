@@ -37,8 +37,8 @@ int check_group(int group, int nb) {
 float effective_scale(const pasa_shape_t* s) { return s->scale > 0.f ? s->scale : 1.0f / sqrtf((float)s->d); }
 
 struct AttnWorkspace {
-  size_t kbar, vs, hg, partial, total;
-  int n_groups, unit, n_units;
+  size_t st, hg, partial, total;
+  int n_groups, unit, n_units, n_chunks;
 };
 
 AttnWorkspace carve_attn(const pasa_shape_t* s) {
@@ -50,9 +50,9 @@ AttnWorkspace carve_attn(const pasa_shape_t* s) {
   w.n_groups = (nb + group - 1) / group;
   w.unit = group < 32 ? group : 32;
   w.n_units = (nb + w.unit - 1) / w.unit;
+  w.n_chunks = (nb + 31) / 32;
   size_t off = 0;
-  w.kbar = off; off = align_up(off + bh * nb * s->d * 2);
-  w.vs = off; off = align_up(off + bh * nb * s->d * 2);
+  w.st = off; off = align_up(off + bh * w.n_chunks * 64 * s->d * 2);
   w.hg = off; off = align_up(off + bh * w.n_groups * s->d * s->d * 2);
   w.partial = off; off = align_up(off + bh * w.n_units * s->d * s->d * 4);
   w.total = off;
@@ -169,8 +169,8 @@ int pasa_kv_stats(const void* k, const void* v, const pasa_shape_t* shape, void*
   t.bh = s.B * s.H; t.H = s.H; t.n = s.n; t.nb = nb; t.block = s.block; t.tail = s.n - (nb - 1) * s.block; t.d = s.d;
   t.group = s.group >= nb ? nb : s.group; t.n_groups = w.n_groups; t.unit = w.unit; t.n_units = w.n_units;
   t.scale = effective_scale(&s);
-  t.kbar = reinterpret_cast<uint16_t*>(base + w.kbar);
-  t.vs = reinterpret_cast<uint16_t*>(base + w.vs);
+  t.n_chunks = w.n_chunks;
+  t.st = reinterpret_cast<uint16_t*>(base + w.st);
   t.hg = reinterpret_cast<uint16_t*>(base + w.hg);
   t.partial = reinterpret_cast<float*>(base + w.partial);
   return pasa_launch_kv_stats(t, static_cast<hipStream_t>(stream)) == hipSuccess ? PASA_OK : PASA_EHIP;
@@ -205,10 +205,10 @@ static int attn_common(const void* q, const void* k, const void* v, const pasa_s
   if (sparse) {
     a.idx = idx; a.mask = mask; a.k_sel = k_sel; a.mask_words = (nb + 31) / 32;
     a.group = s.group >= nb ? nb : s.group;
-    a.kbar = reinterpret_cast<const uint16_t*>(base + w.kbar);
-    a.vs = reinterpret_cast<const uint16_t*>(base + w.vs);
+    a.st = reinterpret_cast<const uint16_t*>(base + w.st);
     a.hg = reinterpret_cast<const uint16_t*>(base + w.hg);
     a.n_groups = w.n_groups;
+    a.n_chunks = w.n_chunks;
   }
   return pasa_launch_attn(a, sparse, s.d, static_cast<hipStream_t>(stream)) == hipSuccess ? PASA_OK : PASA_EHIP;
 }

@@ -26,7 +26,20 @@ struct WaveState {
   float l;             // this lane's share of the running normaliser
 };
 
-// One 64-key tile: logits, online softmax, accumulate.  n_valid = number of valid keys (rows) in
+// Raise the running maximum of a lane to m_new and rescale its accumulators.  Called only when some
+// lane of the wave needs it (the branch around it is wave-uniform).
+template <int D>
+PASA_DEVICE void rescale(WaveState<D>& w, float m_new) {
+  const float corr = __builtin_amdgcn_exp2f(w.m - m_new);  // exp2(-inf) = 0 on the first tile
+  w.m = m_new;
+  w.l *= corr;
+#pragma unroll
+  for (int t = 0; t < D / 32; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) w.o[t][r] *= corr;
+}
+
+// One 64-key tile: logits, online softmax, P^T fragments.  n_valid = number of valid keys (rows) in
 // the tile, may be <= 0 (nothing valid) or >= 64 (all valid).
 template <int D>
 PASA_DEVICE void exact_tile_scores(const char* k_lds, WaveState<D>& w, float c, int n_valid, int lane,
@@ -49,10 +62,9 @@ PASA_DEVICE void exact_tile_scores(const char* k_lds, WaveState<D>& w, float c, 
   float mx = fmaxf(s0[0], s1[0]);
 #pragma unroll
   for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(s0[r], s1[r]));
-  mx = half_swap_max(mx);
-  const float m_new = fmaxf(w.m, mx * c);
-  const float corr = __builtin_amdgcn_exp2f(w.m - m_new);
-  const float neg = -m_new;
+  mx = half_swap_max(mx) * c;
+  if (__builtin_amdgcn_ballot_w64(mx > w.m)) rescale<D>(w, fmaxf(w.m, mx));
+  const float neg = -w.m;
   float sum = 0.f;
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
@@ -60,12 +72,7 @@ PASA_DEVICE void exact_tile_scores(const char* k_lds, WaveState<D>& w, float c, 
     s1[r] = __builtin_amdgcn_exp2f(fmaf(s1[r], c, neg));
     sum += s0[r] + s1[r];
   }
-  w.l = w.l * corr + sum;
-  w.m = m_new;
-#pragma unroll
-  for (int t = 0; t < D / 32; ++t)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) w.o[t][r] *= corr;
+  w.l += sum;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     pf[0][i] = (__bf16)s0[i];
@@ -85,10 +92,11 @@ PASA_DEVICE void exact_tile_pv(const char* v_lds, WaveState<D>& w, const bf16x8 
 
 // Approximation of one chunk of 32 key blocks (Eq.4 and Eq.14).  k_lds rows 0..31 hold the block-mean
 // keys, v_lds rows 0..31 the block value sums.  `word` has bit x set iff block 32*chunk + x is
-// selected; blocks at or beyond nb do not exist.
+// selected; blocks at or beyond nb do not exist.  On return a[r] = a_j of the block in register r
+// (0 for selected or absent blocks) and pf holds the same values as P^T fragments.
 template <int D>
 PASA_DEVICE void approx_chunk_scores(const char* k_lds, WaveState<D>& w, float c, uint32_t word, int chunk,
-                                     int nb, int block, int tail, int lane, f32x16& a_out, bf16x8 (&pf)[2]) {
+                                     int nb, int block, int tail, int lane, f32x16& a, bf16x8 (&pf)[2]) {
   const int h = lane >> 5;
   f32x16 z = {0};
 #pragma unroll
@@ -101,67 +109,117 @@ PASA_DEVICE void approx_chunk_scores(const char* k_lds, WaveState<D>& w, float c
     z[r] = unsel ? z[r] : -INFINITY;
     mx = fmaxf(mx, z[r]);
   }
-  mx = half_swap_max(mx);
-  const float m_new = fmaxf(w.m, mx * c);
-  const float corr = __builtin_amdgcn_exp2f(w.m - m_new);
-  const float neg = -m_new;
+  mx = half_swap_max(mx) * c;
+  if (__builtin_amdgcn_ballot_w64(mx > w.m)) rescale<D>(w, fmaxf(w.m, mx));
+  const float neg = -w.m;
   float sum = 0.f;
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     int j = 32 * chunk + mfma_row(r, h);
-    float a = __builtin_amdgcn_exp2f(fmaf(z[r], c, neg));  // exp2(-inf) = 0 for selected / absent blocks
-    z[r] = a;
-    sum += a * (float)((j == nb - 1) ? tail : block);      // b_j a_j: this block's share of the normaliser
+    z[r] = __builtin_amdgcn_exp2f(fmaf(z[r], c, neg));    // exp2(-inf) = 0 for selected / absent blocks
+    sum += z[r] * (float)((j == nb - 1) ? tail : block);  // b_j a_j: this block's share of the normaliser
   }
-  w.l = w.l * corr + sum;
-  w.m = m_new;
-#pragma unroll
-  for (int t = 0; t < D / 32; ++t)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) w.o[t][r] *= corr;
+  w.l += sum;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     pf[0][i] = (__bf16)z[i];
     pf[1][i] = (__bf16)z[8 + i];
   }
-  a_out = z;
+  a = z;
 }
 
 template <int D>
-PASA_DEVICE void approx_chunk_pv(const char* v_lds, WaveState<D>& w, const bf16x8 (&pf)[2], int lane) {
+PASA_DEVICE void approx_chunk_pv(const char* st_lds, WaveState<D>& w, const bf16x8 (&pf)[2], int lane) {
 #pragma unroll
-  for (int ks = 0; ks < 2; ++ks)
+  for (int ks = 0; ks < 2; ++ks)  // block value sums live in rows 32..63 of the statistics tile
 #pragma unroll
-    for (int t = 0; t < D / 32; ++t) w.o[t] = mfma32(col_frag<D>(v_lds, 16 * ks, 32 * t, lane), pf[ks], w.o[t]);
+    for (int t = 0; t < D / 32; ++t)
+      w.o[t] = mfma32(col_frag<D>(st_lds, 32 + 16 * ks, 32 * t, lane), pf[ks], w.o[t]);
 }
 
-// First-order term of one group inside a chunk: O^T += (scale Hg)^T (Q^T diag(A)), A = sum of the
-// chunk's a_j over the unselected blocks that belong to the group.  hg points at the group's matrix
-// in operand order: [D/32 tiles][D/16 steps][64 lanes][8] bf16 (see the statistics kernel).
+// First-order term of one group (Eq.14), one half of the value columns: O^T[half] += (scale Hg)^T (Q^T diag(A)),
+// A = sum of the chunk's a_j over the unselected blocks of the group.  h_lds holds rows
+// [half*D/2, (half+1)*D/2) of (scale Hg)^T as a K-like tile (row = value column, col = key column).
 template <int D>
-PASA_DEVICE void first_order(const uint16_t* hg, WaveState<D>& w, float A, int lane) {
-  bf16x8 qs[D / 16];
+PASA_DEVICE void first_order_half(const char* h_lds, WaveState<D>& w, float A, int half, int lane) {
 #pragma unroll
-  for (int s = 0; s < D / 16; ++s)
+  for (int s = 0; s < D / 16; ++s) {
+    bf16x8 qs;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) qs[s][i] = (__bf16)((float)w.qf[s][i] * A);
-  const uint4* frag = reinterpret_cast<const uint4*>(hg) + lane;
+    for (int i = 0; i < 8; ++i) qs[i] = (__bf16)((float)w.qf[s][i] * A);
 #pragma unroll
-  for (int t = 0; t < D / 32; ++t)
-#pragma unroll
-    for (int s = 0; s < D / 16; ++s) {
-      uint4 raw = frag[(t * (D / 16) + s) * 64];
-      w.o[t] = mfma32(__builtin_bit_cast(bf16x8, raw), qs[s], w.o[t]);
+    for (int tt = 0; tt < D / 64; ++tt) {
+      const bf16x8 a = row_frag<D>(h_lds, 32 * tt, s, lane);
+      if (half == 0) w.o[tt] = mfma32(a, qs, w.o[tt]);
+      else w.o[D / 64 + tt] = mfma32(a, qs, w.o[D / 64 + tt]);
     }
+  }
 }
+
+// Direct global -> LDS staging of a tile (no registers in between).  One instruction moves 1 KB:
+// 64 lanes x 16 bytes land at consecutive LDS addresses, i.e. RPI = 1024/(2D) whole tile rows; the
+// XOR swizzle of the LDS layout is applied on the global side (which chunk of its row a lane
+// fetches).  Wave `wave` of NW issues instructions wave, wave + NW, ...  The swizzle pattern of a
+// lane repeats every PER instructions of a wave, so PER lane offsets are kept in registers and the
+// rest of the address is wave-uniform scalar arithmetic.
+template <int D, int NW>
+struct TileDma {
+  static constexpr int CPR = D / 8;                          // 16-byte chunks per row
+  static constexpr int RPI = 1024 / (2 * D);                 // rows per instruction
+  static constexpr int NI = 64 / RPI / NW;                   // instructions per wave for a 64-row tile
+  static constexpr int PER = (D == 128 && NW == 2) ? 2 : 1;  // (NW*RPI*PER) % 16 == 0
+  static_assert((NW * RPI * PER) % 16 == 0, "swizzle period");
+  uint32_t off[PER];  // byte offset of this lane's chunk for instruction i < PER, from the tile's first row
+
+  PASA_DEVICE static int tile_row(int i, int wave, int lane) { return (i * NW + wave) * RPI + lane / CPR; }
+
+  PASA_DEVICE void init(int64_t stride_elems, int wave, int lane) {
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int r = tile_row(i, wave, lane);
+      off[i] = (uint32_t)(r * stride_elems * 2 + (((lane % CPR) ^ swz<D>(r)) << 4));
+    }
+  }
+  // rows [0, ROWS) of the tile whose first row is at `base` (wave-uniform); every row is in bounds
+  template <int ROWS>
+  PASA_DEVICE void issue(const uint16_t* base, int64_t stride_elems, char* lds, int wave) const {
+    const char* b = reinterpret_cast<const char*>(base);
+#pragma unroll
+    for (int i = 0; i < NI * ROWS / 64; ++i) {
+      const char* bi = b + (int64_t)((i / PER) * PER * NW * RPI) * stride_elems * 2;  // uniform
+      __builtin_amdgcn_global_load_lds((gbl_void*)(bi + off[i % PER]), (lds_void*)(lds + (i * NW + wave) * 1024), 16, 0, 0);
+    }
+  }
+  // same, but tile rows at or beyond `valid` (>= 1) re-read row valid-1 (finite stand-ins for
+  // rows that do not exist; the caller masks them out)
+  template <int ROWS>
+  PASA_DEVICE void issue_clamped(const uint16_t* base, int64_t stride_elems, int valid, char* lds, int wave,
+                                 int lane) const {
+    const char* b = reinterpret_cast<const char*>(base);
+#pragma unroll
+    for (int i = 0; i < NI * ROWS / 64; ++i) {
+      const int r = tile_row(i, wave, lane);
+      const int64_t o = (int64_t)min(r, valid - 1) * stride_elems * 2 + (((lane % CPR) ^ swz<D>(r)) << 4);
+      __builtin_amdgcn_global_load_lds((gbl_void*)(b + o), (lds_void*)(lds + (i * NW + wave) * 1024), 16, 0, 0);
+    }
+  }
+};
+
+PASA_DEVICE void wait_dma_and_sync() {
+  __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's direct-to-LDS loads have landed
+  __syncthreads();
+}
+
+typedef __attribute__((address_space(4))) const int32_t const_i32;
+typedef __attribute__((address_space(4))) const uint32_t const_u32;
 
 template <int D, int NW, bool SPARSE>
 __global__ void __launch_bounds__(NW * 64, 2) attn_kernel(AttnParams p) {
-  constexpr int T = NW * 64;
   constexpr int TILE_BYTES = 64 * 2 * D;
-  __shared__ __attribute__((aligned(16))) char smem[2 * TILE_BYTES];
-  char* const k_lds = smem;
-  char* const v_lds = smem + TILE_BYTES;
+  // Two separate arrays (not one array indexed by parity): a pending direct-to-LDS load into one
+  // must not make the compiler stall reads of the other.
+  __shared__ __attribute__((aligned(1024))) char lds_x[TILE_BYTES];
+  __shared__ __attribute__((aligned(1024))) char lds_y[TILE_BYTES];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ql = lane & 31, h = lane >> 5;
@@ -185,83 +243,100 @@ __global__ void __launch_bounds__(NW * 64, 2) attn_kernel(AttnParams p) {
   w.m = -INFINITY;
   w.l = 0.f;
 
-  // ---- the item list: exact 64-key tiles first, then chunks of 32 block statistics ----
+  // ---- the stream of 64-row tiles that passes through LDS, alternating between lds_x and lds_y:
+  //   K_0 V_0 K_1 V_1 ...            exact tiles of the selected blocks (dense: of every block)
+  //   ST_0 H_{g,0} H_{g,1} ST_1 ...  per chunk of 32 key blocks: its statistics tile, then the two
+  //                                  halves of every group matrix the chunk intersects
+  // A tile is requested as soon as the buffer it goes to has been consumed, i.e. two tiles ahead.
   const int tiles_per_block = SPARSE ? p.block / 64 : 1;
   const int n_exact = SPARSE ? p.k_sel * tiles_per_block : (n + 63) / 64;
-  const int n_chunks = (SPARSE && p.group > 0) ? (p.nb + 31) / 32 : 0;
-  const int n_items = n_exact + n_chunks;
-  const int32_t* const idx_row = SPARSE ? p.idx + ((int64_t)bh * p.nb + qt) * p.k_sel : nullptr;
-  const uint32_t* const mask_row = (SPARSE && p.group > 0) ? p.mask + ((int64_t)bh * p.nb + qt) * p.mask_words : nullptr;
-  const uint16_t* const kbar = SPARSE ? p.kbar + (int64_t)bh * p.nb * D : nullptr;
-  const uint16_t* const vsum = SPARSE ? p.vs + (int64_t)bh * p.nb * D : nullptr;
+  const int n_chunks = (SPARSE && p.group > 0) ? p.n_chunks : 0;
+  // routing lists are read through the scalar cache (constant address space): uniform, read-only
+  const_i32* const idx_row = SPARSE ? (const_i32*)(p.idx + ((int64_t)bh * p.nb + qt) * p.k_sel) : nullptr;
+  const_u32* const mask_row = n_chunks ? (const_u32*)(p.mask + ((int64_t)bh * p.nb + qt) * p.mask_words) : nullptr;
+  const uint16_t* const st = n_chunks ? p.st + (int64_t)bh * p.n_chunks * 64 * D : nullptr;
+  const uint16_t* const hg = n_chunks ? p.hg + (int64_t)bh * p.n_groups * D * D : nullptr;
 
-  auto key_row0 = [&](int it) -> int {  // first key row of exact item `it`
+  auto key_row0 = [&](int it) -> int {  // first key row of exact tile `it`
     if constexpr (SPARSE) {
-      int j = idx_row[it / tiles_per_block];
+      const int j = idx_row[it / tiles_per_block];
       return j * p.block + (it % tiles_per_block) * 64;
     } else {
       return it * 64;
     }
   };
 
-  TileStage<D, T> st;
-  auto load_k = [&](int it) {
-    if (it < n_exact) st.load(kb, p.stride_n, key_row0(it), 64, n, tid);
-    else st.load(kbar, D, 32 * (it - n_exact), 32, p.nb, tid);
-  };
-  auto load_v = [&](int it) {
-    if (it < n_exact) st.load(vb, p.stride_n, key_row0(it), 64, n, tid);
-    else st.load(vsum, D, 32 * (it - n_exact), 32, p.nb, tid);
-  };
-  auto rows_of = [&](int it) { return it < n_exact ? 64 : 32; };
+  TileDma<D, NW> dma_kv, dma_st;  // lane offsets for rows of K/V (caller's stride) and of workspace tiles (stride D)
+  dma_kv.init(p.stride_n, wave, lane);
+  if (n_chunks) dma_st.init(D, wave, lane);
 
-  load_k(0);
-  st.store(k_lds, rows_of(0), tid);
-  load_v(0);
-  st.store(v_lds, rows_of(0), tid);
-  __syncthreads();
+  auto stage_exact = [&](const uint16_t* src, int r0, char* lds) {
+    const int valid = n - r0;
+    const uint16_t* base = src + (int64_t)r0 * p.stride_n;
+    if (valid >= 64) dma_kv.template issue<64>(base, p.stride_n, lds, wave);
+    else if (valid >= 1) dma_kv.template issue_clamped<64>(base, p.stride_n, valid, lds, wave, lane);
+    // valid <= 0: the tile does not exist (second half of a short last block); every logit of it is
+    // masked and the stale, finite LDS contents meet zero weights
+  };
+  auto stage_stats = [&](int chunk, char* lds) { dma_st.template issue<64>(st + (int64_t)chunk * 64 * D, D, lds, wave); };
+  auto stage_hg = [&](int g, int half, char* lds) {
+    dma_st.template issue<D / 2>(hg + ((int64_t)g * D + half * (D / 2)) * D, D, lds, wave);
+  };
+  auto first_group = [&](int chunk) { return (32 * chunk) / p.group; };
+  auto last_group = [&](int chunk) { return (min(32 * chunk + 32, p.nb) - 1) / p.group; };
 
-  for (int it = 0; it < n_items; ++it) {
-    const bool has_next = it + 1 < n_items;
-    if (has_next) load_k(it + 1);
-    if (it < n_exact) {
-      bf16x8 pf[4];
-      const int n_valid = n - key_row0(it);
-      exact_tile_scores<D>(k_lds, w, p.c, n_valid, lane, pf);
-      __syncthreads();  // every wave has read the K tile
-      if (has_next) {
-        st.store(k_lds, rows_of(it + 1), tid);
-        load_v(it + 1);
-      }
-      exact_tile_pv<D>(v_lds, w, pf, lane);
-    } else {
-      const int chunk = it - n_exact;
-      const uint32_t word = mask_row[chunk];
-      bf16x8 pf[2];
-      f32x16 a;
-      approx_chunk_scores<D>(k_lds, w, p.c, word, chunk, p.nb, p.block, p.tail, lane, a, pf);
-      __syncthreads();
-      if (has_next) {
-        st.store(k_lds, rows_of(it + 1), tid);
-        load_v(it + 1);
-      }
-      approx_chunk_pv<D>(v_lds, w, pf, lane);
-      // first-order term, one pass per group that intersects this chunk
-      const int j_lo = 32 * chunk, j_hi = min(j_lo + 32, p.nb);
-      for (int g = j_lo / p.group; g <= (j_hi - 1) / p.group; ++g) {
-        float A = 0.f;
+  // ---------------- exact tiles: K in lds_x, V in lds_y ----------------
+  int r0 = key_row0(0);
+  stage_exact(kb, r0, lds_x);
+  wait_dma_and_sync();
+  stage_exact(vb, r0, lds_y);
+  for (int it = 0; it < n_exact; ++it) {
+    const bool more = it + 1 < n_exact;
+    const int r0_next = more ? key_row0(it + 1) : 0;
+    bf16x8 pf[4];
+    exact_tile_scores<D>(lds_x, w, p.c, n - r0, lane, pf);
+    wait_dma_and_sync();  // V tile visible to every wave; every wave is done with the K tile
+    if (more) stage_exact(kb, r0_next, lds_x);
+    else if (n_chunks) stage_stats(0, lds_x);
+    exact_tile_pv<D>(lds_y, w, pf, lane);
+    wait_dma_and_sync();  // next K (or first statistics tile) visible; every wave is done with the V tile
+    if (more) stage_exact(vb, r0_next, lds_y);
+    else if (n_chunks) stage_hg(first_group(0), 0, lds_y);
+    r0 = r0_next;
+  }
+
+  // ---------------- grouped approximation of the unselected blocks ----------------
+  // On entry of a chunk: its statistics tile is visible in `ps`, the first half of its first group
+  // matrix is on its way to `pq`.  The two buffers swap roles from one chunk to the next.
+  auto approx_chunk = [&](int chunk, char* ps, char* pq) {
+    bf16x8 pf[2];
+    f32x16 a;
+    approx_chunk_scores<D>(ps, w, p.c, mask_row[chunk], chunk, p.nb, p.block, p.tail, lane, a, pf);
+    approx_chunk_pv<D>(ps, w, pf, lane);
+    const bool more = chunk + 1 < n_chunks;
+    const int g_last = last_group(chunk);
+    for (int g = first_group(chunk); g <= g_last; ++g) {
+      float A = 0.f;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          int j = j_lo + mfma_row(r, h);
-          A += (j / p.group == g) ? a[r] : 0.f;
-        }
-        A = half_swap_sum(A);
-        first_order<D>(p.hg + ((int64_t)bh * p.n_groups + g) * D * D, w, A, lane);
+      for (int r = 0; r < 16; ++r) {
+        const int j = 32 * chunk + mfma_row(r, h);
+        A += (j / p.group == g) ? a[r] : 0.f;
       }
+      A = half_swap_sum(A);
+      wait_dma_and_sync();  // first half of Hg visible in pq; ps is free
+      stage_hg(g, 1, ps);
+      first_order_half<D>(pq, w, A, 0, lane);
+      wait_dma_and_sync();  // second half visible in ps; pq is free
+      if (g < g_last) stage_hg(g + 1, 0, pq);
+      else if (more) stage_stats(chunk + 1, pq);
+      first_order_half<D>(ps, w, A, 1, lane);
     }
-    __syncthreads();  // every wave has read the V tile
-    if (has_next) st.store(v_lds, rows_of(it + 1), tid);
-    __syncthreads();  // next K and V tiles are visible
+    wait_dma_and_sync();  // next statistics tile visible in pq; ps is free
+    if (more) stage_hg(first_group(chunk + 1), 0, ps);
+  };
+  for (int chunk = 0; chunk < n_chunks; chunk += 2) {
+    approx_chunk(chunk, lds_x, lds_y);
+    if (chunk + 1 < n_chunks) approx_chunk(chunk + 1, lds_y, lds_x);
   }
 
   // ---- epilogue: normalise and write ----

@@ -19,10 +19,10 @@ struct AttnParams {
   const int32_t* idx;
   const uint32_t* mask;
   int32_t k_sel, mask_words;
-  const uint16_t* kbar;  // bf16 [BH][nb][d]   block-mean keys
-  const uint16_t* vs;    // bf16 [BH][nb][d]   block value sums
-  const uint16_t* hg;    // bf16 [BH][n_groups][d*d] scaled group matrices in MFMA operand order
-  int32_t group, n_groups;
+  const uint16_t* st;    // bf16 [BH][n_chunks][64][d]: rows 0..31 block-mean keys, rows 32..63 block value
+                         // sums of key blocks 32c..32c+31 (zero rows for blocks that do not exist)
+  const uint16_t* hg;    // bf16 [BH][n_groups][d][d]: (scale * Hg)^T, row = value column, col = key column
+  int32_t group, n_groups, n_chunks;
 };
 
 // dense (sparse = false) or piecewise sparse attention; d in {64,128}, block in {64,128}
@@ -38,10 +38,10 @@ struct StatsParams {
   int32_t unit;      // blocks summed by one workgroup: min(group, 32)
   int32_t n_units;   // units per head
   float scale;
-  uint16_t* kbar;    // out bf16 [BH][nb][d]
-  uint16_t* vs;      // out bf16 [BH][nb][d]
+  int32_t n_chunks;  // ceil(nb / 32)
+  uint16_t* st;      // out bf16 [BH][n_chunks][64][d] (see AttnParams::st)
   float* partial;    // scratch fp32 [BH][n_units][d][d]: sum over the unit's blocks of H_j
-  uint16_t* hg;      // out bf16 [BH][n_groups][d*d], operand order, times scale
+  uint16_t* hg;      // out bf16 [BH][n_groups][d][d] (see AttnParams::hg)
 };
 hipError_t pasa_launch_kv_stats(const StatsParams& p, hipStream_t stream);
 

@@ -1,7 +1,8 @@
 // Key/value block statistics of the PASA forward (Eq.4's inner sum, Eq.5, Eq.12) for gfx950.
 //
-//   Kbar_j = mean_n K_{j,n}              -> bf16 [BH][N_B][d]
-//   VS_j   = sum_n  V_{j,n}              -> bf16 [BH][N_B][d]
+//   Kbar_j = mean_n K_{j,n}   -> bf16, row (j & 31)      of tile [BH][j >> 5][64][d]
+//   VS_j   = sum_n  V_{j,n}   -> bf16, row 32 + (j & 31) of the same tile (one tile = one chunk of 32
+//                                 blocks, laid out so the attention kernel streams it like a K tile)
 //   Hg_g   = mean_{j in group g} H_j,  H_j = sum_n (K_{j,n} - Kbar_j)^T V_{j,n} = K_j^T V_j - Kbar_j^T VS_j
 //
 // H_j is never written to memory.  A workgroup owns a "unit" of consecutive blocks (a whole group
@@ -9,8 +10,8 @@
 // matrix cores with fp32 accumulators (both operands are fetched from the row-major LDS tiles with
 // transposing LDS reads, the contraction runs over tokens), subtracts the rank-one term of every
 // block in fp32, and writes the unit's sum.  A second small kernel averages the units of a group,
-// applies the logit scale and stores the matrix as bf16 in the order the attention kernel's MFMA
-// consumes it.
+// applies the logit scale and stores the transposed matrix as bf16, row-major [value column][key
+// column], which the attention kernel streams through LDS exactly like a K tile.
 #include "pasa_device.hpp"
 #include "pasa_kernels.hpp"
 
@@ -87,10 +88,10 @@ __global__ void __launch_bounds__(256) kv_stats_kernel(StatsParams p) {
       if (is_k_col) {
         const float mean = colsum / (float)len;
         kmean_s[col] = mean;
-        p.kbar[((int64_t)bh * p.nb + j) * D + col] = __builtin_bit_cast(uint16_t, (__bf16)mean);
+        p.st[(((int64_t)bh * p.n_chunks + (j >> 5)) * 64 + (j & 31)) * D + col] = __builtin_bit_cast(uint16_t, (__bf16)mean);
       } else if (is_v_col) {
         vsum_s[col] = colsum;
-        p.vs[((int64_t)bh * p.nb + j) * D + col] = __builtin_bit_cast(uint16_t, (__bf16)colsum);
+        p.st[(((int64_t)bh * p.n_chunks + (j >> 5)) * 64 + 32 + (j & 31)) * D + col] = __builtin_bit_cast(uint16_t, (__bf16)colsum);
       }
       colsum = 0.f;
     }
@@ -107,6 +108,11 @@ __global__ void __launch_bounds__(256) kv_stats_kernel(StatsParams p) {
     }
   }
 
+  if (j_hi == p.nb && (is_k_col || is_v_col)) {  // rows of blocks that do not exist read as zero
+    for (int j = p.nb; j < 32 * p.n_chunks; ++j)
+      p.st[(((int64_t)bh * p.n_chunks + (j >> 5)) * 64 + (is_v_col ? 32 : 0) + (j & 31)) * D + col] = 0;
+  }
+
   float* out = p.partial + ((int64_t)bh * p.n_units + u) * D * D;
 #pragma unroll
   for (int a = 0; a < TI; ++a)
@@ -117,8 +123,7 @@ __global__ void __launch_bounds__(256) kv_stats_kernel(StatsParams p) {
         out[(32 * (tin0 + a) + mfma_row(r, h)) * D + 32 * (tout0 + b) + (lane & 31)] = acc[a][b][r];
 }
 
-// partial [BH][n_units][d_in][d_out] fp32 -> hg [BH][n_groups] in operand order:
-// element ((t*(D/16) + s)*64 + lane)*8 + i  =  scale * Hg[d_in = 16s + 8(lane>>5) + i][d_out = 32t + (lane&31)]
+// partial [BH][n_units][d_in][d_out] fp32 -> hg [BH][n_groups][d_out][d_in] bf16 = (scale * Hg)^T
 template <int D>
 __global__ void __launch_bounds__(256) hg_finish_kernel(StatsParams p) {
   const int g = blockIdx.x, bh = blockIdx.y;
@@ -129,19 +134,16 @@ __global__ void __launch_bounds__(256) hg_finish_kernel(StatsParams p) {
   const float f = p.scale / (float)blocks_in_group;
   const float* part = p.partial + (int64_t)bh * p.n_units * D * D;
   uint16_t* out = p.hg + ((int64_t)bh * p.n_groups + g) * D * D;
-  for (int f8 = threadIdx.x; f8 < D * D / 8; f8 += 256) {  // one 16-byte operand fragment per thread
-    const int l = f8 & 63, ts = f8 >> 6;
-    const int s = ts % (D / 16), t = ts / (D / 16);
-    const int d_out = 32 * t + (l & 31);
+  for (int x = threadIdx.x; x < D * D / 8; x += 256) {  // 8 consecutive key columns of one value column
+    const int d_out = x % D, d_in0 = (x / D) * 8;
     bf16x8 v;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const int d_in = 16 * s + 8 * (l >> 5) + i;
       float sum = 0.f;
-      for (int u = u_lo; u < u_hi; ++u) sum += part[((int64_t)u * D + d_in) * D + d_out];
+      for (int u = u_lo; u < u_hi; ++u) sum += part[((int64_t)u * D + d_in0 + i) * D + d_out];
       v[i] = (__bf16)(sum * f);
     }
-    *reinterpret_cast<bf16x8*>(out + (int64_t)f8 * 8) = v;
+    *reinterpret_cast<bf16x8*>(out + (int64_t)d_out * D + d_in0) = v;
   }
 }
 
