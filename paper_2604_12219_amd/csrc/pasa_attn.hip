@@ -17,6 +17,7 @@ namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
+constexpr int kXcds = 8;  // accelerator complex dies of an MI355X
 
 template <int D>
 struct WaveState {
@@ -223,7 +224,13 @@ __global__ void __launch_bounds__(NW * 64, 2) attn_kernel(AttnParams p) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int ql = lane & 31, h = lane >> 5;
-  const int bh = blockIdx.x / p.q_tiles, qt = blockIdx.x % p.q_tiles;
+  // Workgroup -> (head, query tile).  The hardware deals consecutive workgroup ids round-robin to
+  // the 8 XCDs (each with its own L2), so ids are decoded such that one XCD owns a contiguous run
+  // of query tiles of one head and all XCDs work on the same head at the same time: neighbouring
+  // query tiles select overlapping key blocks and walk them in the same (ascending) order.
+  const int xcd = blockIdx.x % kXcds, local = blockIdx.x / kXcds;
+  const int bh = local / p.q_tiles_per_xcd, qt = xcd * p.q_tiles_per_xcd + local % p.q_tiles_per_xcd;
+  if (qt >= p.q_tiles) return;  // padding workgroup (whole workgroup leaves before any barrier)
   const int64_t head_off = (int64_t)(bh / p.H) * p.stride_b + (int64_t)(bh % p.H) * p.stride_h;
   const uint16_t* const qb = p.q + head_off;
   const uint16_t* const kb = p.k + head_off;
@@ -370,14 +377,16 @@ hipError_t pasa_launch_attn(AttnParams p, bool sparse, int d, hipStream_t stream
   p.c = p.scale * kLog2e;
   if (sparse) {
     p.q_tiles = p.nb;  // one workgroup per query block
-    const int grid = p.bh * p.q_tiles;
+    p.q_tiles_per_xcd = (p.q_tiles + kXcds - 1) / kXcds;
+    const int grid = p.bh * kXcds * p.q_tiles_per_xcd;
     if (d == 128 && p.block == 64) return launch<128, 2, true>(p, grid, stream);
     if (d == 128 && p.block == 128) return launch<128, 4, true>(p, grid, stream);
     if (d == 64 && p.block == 64) return launch<64, 2, true>(p, grid, stream);
     if (d == 64 && p.block == 128) return launch<64, 4, true>(p, grid, stream);
   } else {
     p.q_tiles = (p.n + 127) / 128;
-    const int grid = p.bh * p.q_tiles;
+    p.q_tiles_per_xcd = (p.q_tiles + kXcds - 1) / kXcds;
+    const int grid = p.bh * kXcds * p.q_tiles_per_xcd;
     if (d == 128) return launch<128, 4, false>(p, grid, stream);
     if (d == 64) return launch<64, 4, false>(p, grid, stream);
   }

@@ -14,7 +14,7 @@ struct AttnParams {
   int64_t stride_b, stride_h, stride_n;
   int32_t bh, H, n, nb, block, tail;  // tail = valid tokens of the last block
   float scale, c;                     // c = scale * log2(e), filled in by the launcher
-  int32_t q_tiles;                    // filled in by the launcher
+  int32_t q_tiles, q_tiles_per_xcd;   // filled in by the launcher
   // sparse path only
   const int32_t* idx;
   const uint32_t* mask;
