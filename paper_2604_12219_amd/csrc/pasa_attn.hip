@@ -10,6 +10,16 @@
 // A wave owns 32 query rows; lane (q = lane & 31, h = lane >> 5) holds for query q the logits of
 // the keys 8g + 4h + r of each 32-key sub-tile (g, r = 0..3), so the row maximum and row sum are
 // in-lane reductions plus one exchange with lane ^ 32.
+//
+// Work decomposition.  A workgroup is 4 waves = 128 query rows: one query block of 128 tokens, or
+// TWO ADJACENT query blocks of 64 tokens (waves 0,1 and waves 2,3).  In the second case the
+// workgroup walks the UNION of the two ascending block lists; a tile is staged in LDS once and each
+// wave pair computes on it only if its own list contains the block.  Adjacent query blocks of a
+// video select heavily overlapping key blocks, so this cuts the K/V traffic per query block.
+//
+// Data movement.  All tiles (K, V, block statistics, group matrices) are 64-row tiles that stream
+// through a ring of four LDS buffers by direct global->LDS loads, requested three tiles ahead of
+// their use; one workgroup barrier per tile.
 #include "pasa_device.hpp"
 #include "pasa_kernels.hpp"
 
@@ -17,7 +27,14 @@ namespace {
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-constexpr int kXcds = 8;  // accelerator complex dies of an MI355X
+constexpr int kXcds = 8;    // accelerator complex dies of an MI355X, each with its own L2
+constexpr int kWaves = 4;   // waves per workgroup
+constexpr int kRing = 4;    // LDS tile buffers
+constexpr int kAhead = 3;   // a tile is requested this many tiles before it is consumed
+constexpr int kNoBlock = 0x7fffffff;
+
+typedef __attribute__((address_space(4))) const int32_t const_i32;
+typedef __attribute__((address_space(4))) const uint32_t const_u32;
 
 template <int D>
 struct WaveState {
@@ -91,17 +108,17 @@ PASA_DEVICE void exact_tile_pv(const char* v_lds, WaveState<D>& w, const bf16x8 
     for (int t = 0; t < D / 32; ++t) w.o[t] = mfma32(col_frag<D>(v_lds, 16 * ks, 32 * t, lane), pf[ks], w.o[t]);
 }
 
-// Approximation of one chunk of 32 key blocks (Eq.4 and Eq.14).  k_lds rows 0..31 hold the block-mean
-// keys, v_lds rows 0..31 the block value sums.  `word` has bit x set iff block 32*chunk + x is
-// selected; blocks at or beyond nb do not exist.  On return a[r] = a_j of the block in register r
-// (0 for selected or absent blocks) and pf holds the same values as P^T fragments.
+// Zeroth-order part of one chunk of 32 key blocks (Eq.4).  Rows 0..31 of the statistics tile hold
+// the block-mean keys, rows 32..63 the block value sums.  `word` has bit x set iff block
+// 32*chunk + x is selected; blocks at or beyond nb do not exist.  On return a[r] = a_j of the block
+// in register r (0 for selected or absent blocks).
 template <int D>
-PASA_DEVICE void approx_chunk_scores(const char* k_lds, WaveState<D>& w, float c, uint32_t word, int chunk,
-                                     int nb, int block, int tail, int lane, f32x16& a, bf16x8 (&pf)[2]) {
+PASA_DEVICE void approx_chunk_zeroth(const char* st_lds, WaveState<D>& w, float c, uint32_t word, int chunk, int nb,
+                                     int block, int tail, int lane, f32x16& a) {
   const int h = lane >> 5;
   f32x16 z = {0};
 #pragma unroll
-  for (int s = 0; s < D / 16; ++s) z = mfma32(row_frag<D>(k_lds, 0, s, lane), w.qf[s], z);
+  for (int s = 0; s < D / 16; ++s) z = mfma32(row_frag<D>(st_lds, 0, s, lane), w.qf[s], z);
   float mx = -INFINITY;
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
@@ -121,122 +138,148 @@ PASA_DEVICE void approx_chunk_scores(const char* k_lds, WaveState<D>& w, float c
     sum += z[r] * (float)((j == nb - 1) ? tail : block);  // b_j a_j: this block's share of the normaliser
   }
   w.l += sum;
+  bf16x8 pf[2];
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     pf[0][i] = (__bf16)z[i];
     pf[1][i] = (__bf16)z[8 + i];
   }
-  a = z;
-}
-
-template <int D>
-PASA_DEVICE void approx_chunk_pv(const char* st_lds, WaveState<D>& w, const bf16x8 (&pf)[2], int lane) {
 #pragma unroll
-  for (int ks = 0; ks < 2; ++ks)  // block value sums live in rows 32..63 of the statistics tile
+  for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
     for (int t = 0; t < D / 32; ++t)
       w.o[t] = mfma32(col_frag<D>(st_lds, 32 + 16 * ks, 32 * t, lane), pf[ks], w.o[t]);
+  a = z;
 }
 
-// First-order term of one group (Eq.14), one half of the value columns: O^T[half] += (scale Hg)^T (Q^T diag(A)),
+// First-order term of one group (Eq.14), 64 value columns at a time: O^T[part] += (scale Hg)^T (Q^T diag(A)),
 // A = sum of the chunk's a_j over the unselected blocks of the group.  h_lds holds rows
-// [half*D/2, (half+1)*D/2) of (scale Hg)^T as a K-like tile (row = value column, col = key column).
+// [64*part, 64*part + 64) of (scale Hg)^T as a K-like tile (row = value column, col = key column).
 template <int D>
-PASA_DEVICE void first_order_half(const char* h_lds, WaveState<D>& w, float A, int half, int lane) {
+PASA_DEVICE void first_order_part(const char* h_lds, WaveState<D>& w, float A, int part, int lane) {
 #pragma unroll
   for (int s = 0; s < D / 16; ++s) {
     bf16x8 qs;
 #pragma unroll
     for (int i = 0; i < 8; ++i) qs[i] = (__bf16)((float)w.qf[s][i] * A);
-#pragma unroll
-    for (int tt = 0; tt < D / 64; ++tt) {
-      const bf16x8 a = row_frag<D>(h_lds, 32 * tt, s, lane);
-      if (half == 0) w.o[tt] = mfma32(a, qs, w.o[tt]);
-      else w.o[D / 64 + tt] = mfma32(a, qs, w.o[D / 64 + tt]);
+    const bf16x8 a0 = row_frag<D>(h_lds, 0, s, lane), a1 = row_frag<D>(h_lds, 32, s, lane);
+    if (D == 64 || part == 0) {
+      w.o[0] = mfma32(a0, qs, w.o[0]);
+      w.o[1] = mfma32(a1, qs, w.o[1]);
+    } else {
+      w.o[D / 32 - 2] = mfma32(a0, qs, w.o[D / 32 - 2]);
+      w.o[D / 32 - 1] = mfma32(a1, qs, w.o[D / 32 - 1]);
     }
   }
 }
 
-// Direct global -> LDS staging of a tile (no registers in between).  One instruction moves 1 KB:
-// 64 lanes x 16 bytes land at consecutive LDS addresses, i.e. RPI = 1024/(2D) whole tile rows; the
-// XOR swizzle of the LDS layout is applied on the global side (which chunk of its row a lane
-// fetches).  Wave `wave` of NW issues instructions wave, wave + NW, ...  The swizzle pattern of a
-// lane repeats every PER instructions of a wave, so PER lane offsets are kept in registers and the
-// rest of the address is wave-uniform scalar arithmetic.
-template <int D, int NW>
+// ---- direct global -> LDS tile loads ------------------------------------------------------------
+// One instruction moves 1 KB: 64 lanes x 16 bytes land at consecutive LDS addresses starting at M0,
+// i.e. RPI = 1024/(2D) whole tile rows; the XOR swizzle of the LDS layout is applied on the global
+// side (which 16-byte chunk of its row a lane fetches).  Wave w issues instruction slots w, w+4, ...
+// The loads are written as inline assembly so that the compiler's wait-count insertion does not see
+// them (it would serialise every LDS read behind all pending loads); ordering is by the counted
+// waits in ring_barrier().  A wait count the compiler derives for its own loads can only become
+// stricter by loads it does not know about (loads complete in issue order), never too weak.
+PASA_DEVICE void dma_1k(const void* sbase, uint32_t voff, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr), "v"(voff), "s"(sbase)
+               : "memory", "m0");
+}
+
+template <int D>
 struct TileDma {
-  static constexpr int CPR = D / 8;                          // 16-byte chunks per row
-  static constexpr int RPI = 1024 / (2 * D);                 // rows per instruction
-  static constexpr int NI = 64 / RPI / NW;                   // instructions per wave for a 64-row tile
-  static constexpr int PER = (D == 128 && NW == 2) ? 2 : 1;  // (NW*RPI*PER) % 16 == 0
-  static_assert((NW * RPI * PER) % 16 == 0, "swizzle period");
-  uint32_t off[PER];  // byte offset of this lane's chunk for instruction i < PER, from the tile's first row
+  static constexpr int CPR = D / 8;                 // 16-byte chunks per row
+  static constexpr int RPI = 1024 / (2 * D);        // rows per instruction
+  static constexpr int NI = 64 / RPI / kWaves;      // instructions per wave and tile
+  static_assert((kWaves * RPI) % 16 == 0, "a lane's swizzle must not change between its instructions");
 
-  PASA_DEVICE static int tile_row(int i, int wave, int lane) { return (i * NW + wave) * RPI + lane / CPR; }
+  PASA_DEVICE static int tile_row(int i, int wave, int lane) { return (i * kWaves + wave) * RPI + lane / CPR; }
+  PASA_DEVICE static uint32_t chunk_off(int row, int lane) { return (uint32_t)(((lane % CPR) ^ swz<D>(row)) << 4); }
 
-  PASA_DEVICE void init(int64_t stride_elems, int wave, int lane) {
+  // all 64 rows are in bounds.  base, stride: wave-uniform.
+  PASA_DEVICE static void issue(const uint16_t* base, int64_t stride_elems, uint32_t lds, int wave, int lane) {
+    const int r = tile_row(0, wave, lane);
+    const uint32_t voff = (uint32_t)(r * stride_elems * 2) + chunk_off(r, lane);
 #pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const int r = tile_row(i, wave, lane);
-      off[i] = (uint32_t)(r * stride_elems * 2 + (((lane % CPR) ^ swz<D>(r)) << 4));
+    for (int i = 0; i < NI; ++i) {
+      const char* bi = reinterpret_cast<const char*>(base) + (int64_t)(i * kWaves * RPI) * stride_elems * 2;
+      dma_1k(bi, voff, lds + (uint32_t)((i * kWaves + wave) * 1024));
     }
   }
-  // rows [0, ROWS) of the tile whose first row is at `base` (wave-uniform); every row is in bounds
-  template <int ROWS>
-  PASA_DEVICE void issue(const uint16_t* base, int64_t stride_elems, char* lds, int wave) const {
-    const char* b = reinterpret_cast<const char*>(base);
+  // tile rows at or beyond `valid` (>= 1) re-read row valid-1 of the tile (finite stand-ins for rows
+  // that do not exist; the caller masks them out).
+  PASA_DEVICE static void issue_clamped(const uint16_t* base, int64_t stride_elems, int valid, uint32_t lds, int wave,
+                                        int lane) {
 #pragma unroll
-    for (int i = 0; i < NI * ROWS / 64; ++i) {
-      const char* bi = b + (int64_t)((i / PER) * PER * NW * RPI) * stride_elems * 2;  // uniform
-      __builtin_amdgcn_global_load_lds((gbl_void*)(bi + off[i % PER]), (lds_void*)(lds + (i * NW + wave) * 1024), 16, 0, 0);
-    }
-  }
-  // same, but tile rows at or beyond `valid` (>= 1) re-read row valid-1 (finite stand-ins for
-  // rows that do not exist; the caller masks them out)
-  template <int ROWS>
-  PASA_DEVICE void issue_clamped(const uint16_t* base, int64_t stride_elems, int valid, char* lds, int wave,
-                                 int lane) const {
-    const char* b = reinterpret_cast<const char*>(base);
-#pragma unroll
-    for (int i = 0; i < NI * ROWS / 64; ++i) {
+    for (int i = 0; i < NI; ++i) {
       const int r = tile_row(i, wave, lane);
-      const int64_t o = (int64_t)min(r, valid - 1) * stride_elems * 2 + (((lane % CPR) ^ swz<D>(r)) << 4);
-      __builtin_amdgcn_global_load_lds((gbl_void*)(b + o), (lds_void*)(lds + (i * NW + wave) * 1024), 16, 0, 0);
+      const uint32_t voff = (uint32_t)(min(r, valid - 1) * stride_elems * 2) + chunk_off(r, lane);
+      dma_1k(base, voff, lds + (uint32_t)((i * kWaves + wave) * 1024));
     }
   }
 };
 
-PASA_DEVICE void wait_dma_and_sync() {
-  __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's direct-to-LDS loads have landed
-  __syncthreads();
+// Wait until at most `newer` tiles requested after the one about to be read are still in flight
+// (each wave issues NI loads per tile), and until this wave's LDS reads of the previous tile have
+// returned; then meet the other waves.  After the barrier the tile is complete in LDS and the buffer
+// of the previous tile may be overwritten.
+template <int NI>
+PASA_DEVICE void ring_barrier(int newer) {
+  if (newer >= 2) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(2 * NI) : "memory");
+  else if (newer == 1) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(NI) : "memory");
+  else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-typedef __attribute__((address_space(4))) const int32_t const_i32;
-typedef __attribute__((address_space(4))) const uint32_t const_u32;
+// ---- the ascending walk over the union of (up to) two block lists --------------------------------
+struct UnionWalk {
+  const_i32* la;
+  const_i32* lb;
+  int k_a, k_b;        // list lengths (0 = list absent)
+  int ia, ib, va, vb;  // cursors and the block ids under them (kNoBlock when exhausted)
+  int sub;             // 64-key tile within the current block
+  PASA_DEVICE void init(const_i32* a, int ka, const_i32* b, int kb) {
+    la = a; lb = b; k_a = ka; k_b = kb; ia = ib = sub = 0;
+    va = ka > 0 ? a[0] : kNoBlock;
+    vb = kb > 0 ? b[0] : kNoBlock;
+  }
+  PASA_DEVICE bool done() const { return va == kNoBlock && vb == kNoBlock; }
+  PASA_DEVICE int block() const { return min(va, vb); }  // current block id
+  PASA_DEVICE bool in_a() const { return va <= vb; }      // ... and which lists contain it
+  PASA_DEVICE bool in_b() const { return vb <= va; }
+  PASA_DEVICE void advance(int tiles_per_block) {
+    if (++sub < tiles_per_block) return;
+    sub = 0;
+    const int j = min(va, vb);
+    if (va == j) { ++ia; va = ia < k_a ? la[ia] : kNoBlock; }
+    if (vb == j) { ++ib; vb = ib < k_b ? lb[ib] : kNoBlock; }
+  }
+};
 
-template <int D, int NW, bool SPARSE>
-__global__ void __launch_bounds__(NW * 64, 2) attn_kernel(AttnParams p) {
+template <int D, bool SPARSE>
+__global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
   constexpr int TILE_BYTES = 64 * 2 * D;
-  // Two separate arrays (not one array indexed by parity): a pending direct-to-LDS load into one
-  // must not make the compiler stall reads of the other.
-  __shared__ __attribute__((aligned(1024))) char lds_x[TILE_BYTES];
-  __shared__ __attribute__((aligned(1024))) char lds_y[TILE_BYTES];
+  constexpr int NI = TileDma<D>::NI;
+  constexpr int HPARTS = D / 64;  // 64-row tiles per group matrix
+  __shared__ __attribute__((aligned(1024))) char ring[kRing * TILE_BYTES];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int ql = lane & 31, h = lane >> 5;
   // Workgroup -> (head, query tile).  The hardware deals consecutive workgroup ids round-robin to
-  // the 8 XCDs (each with its own L2), so ids are decoded such that one XCD owns a contiguous run
-  // of query tiles of one head and all XCDs work on the same head at the same time: neighbouring
-  // query tiles select overlapping key blocks and walk them in the same (ascending) order.
+  // the 8 XCDs, so ids are decoded such that one XCD owns a contiguous run of query tiles of one
+  // head and all XCDs work on the same head at the same time.
   const int xcd = blockIdx.x % kXcds, local = blockIdx.x / kXcds;
   const int bh = local / p.q_tiles_per_xcd, qt = xcd * p.q_tiles_per_xcd + local % p.q_tiles_per_xcd;
-  if (qt >= p.q_tiles) return;  // padding workgroup (whole workgroup leaves before any barrier)
+  if (qt >= p.q_tiles) return;  // padding workgroup (the whole workgroup leaves before any barrier)
   const int64_t head_off = (int64_t)(bh / p.H) * p.stride_b + (int64_t)(bh % p.H) * p.stride_h;
   const uint16_t* const qb = p.q + head_off;
   const uint16_t* const kb = p.k + head_off;
   const uint16_t* const vb = p.v + head_off;
   const int n = p.n;
-  const int q_row = qt * (NW * 32) + wave * 32 + ql;
+  const int q_row = qt * 128 + wave * 32 + ql;
+  const uint32_t ring_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)ring;
+  auto buf = [&](int item) -> const char* { return ring + (item & (kRing - 1)) * TILE_BYTES; };
+  auto buf_addr = [&](int item) -> uint32_t { return ring_base + (uint32_t)((item & (kRing - 1)) * TILE_BYTES); };
 
   WaveState<D> w;
 #pragma unroll
@@ -250,77 +293,110 @@ __global__ void __launch_bounds__(NW * 64, 2) attn_kernel(AttnParams p) {
   w.m = -INFINITY;
   w.l = 0.f;
 
-  // ---- the stream of 64-row tiles that passes through LDS, alternating between lds_x and lds_y:
-  //   K_0 V_0 K_1 V_1 ...            exact tiles of the selected blocks (dense: of every block)
-  //   ST_0 H_{g,0} H_{g,1} ST_1 ...  per chunk of 32 key blocks: its statistics tile, then the two
-  //                                  halves of every group matrix the chunk intersects
-  // A tile is requested as soon as the buffer it goes to has been consumed, i.e. two tiles ahead.
+  // ---- which query block this wave belongs to, and the block lists of the workgroup ----
+  const int qpw = SPARSE ? 128 / p.block : 1;             // query blocks per workgroup: 1 or 2
+  const bool second = SPARSE && qpw == 2 && (wave >> 1);  // this wave works for the second list
+  const int my_qb = SPARSE ? qt * qpw + (second ? 1 : 0) : 0;
+  const bool qb_exists = !SPARSE || my_qb < p.nb;         // the second block of the last pair may not exist
   const int tiles_per_block = SPARSE ? p.block / 64 : 1;
-  const int n_exact = SPARSE ? p.k_sel * tiles_per_block : (n + 63) / 64;
+  const int n_dense_tiles = (n + 63) / 64;
   const int n_chunks = (SPARSE && p.group > 0) ? p.n_chunks : 0;
-  // routing lists are read through the scalar cache (constant address space): uniform, read-only
-  const_i32* const idx_row = SPARSE ? (const_i32*)(p.idx + ((int64_t)bh * p.nb + qt) * p.k_sel) : nullptr;
-  const_u32* const mask_row = n_chunks ? (const_u32*)(p.mask + ((int64_t)bh * p.nb + qt) * p.mask_words) : nullptr;
   const uint16_t* const st = n_chunks ? p.st + (int64_t)bh * p.n_chunks * 64 * D : nullptr;
   const uint16_t* const hg = n_chunks ? p.hg + (int64_t)bh * p.n_groups * D * D : nullptr;
+  const_u32* const mask_row =
+      (n_chunks && qb_exists) ? (const_u32*)(p.mask + ((int64_t)bh * p.nb + my_qb) * p.mask_words) : nullptr;
 
-  auto key_row0 = [&](int it) -> int {  // first key row of exact tile `it`
+  auto make_walk = [&]() {
+    UnionWalk u;
     if constexpr (SPARSE) {
-      const int j = idx_row[it / tiles_per_block];
-      return j * p.block + (it % tiles_per_block) * 64;
+      const_i32* base = (const_i32*)(p.idx + ((int64_t)bh * p.nb + (int64_t)qt * qpw) * p.k_sel);
+      const bool has_b = qpw == 2 && qt * 2 + 1 < p.nb;
+      u.init(base, p.k_sel, base + p.k_sel, has_b ? p.k_sel : 0);
     } else {
-      return it * 64;
+      u.init(nullptr, 0, nullptr, 0);
     }
-  };
-
-  TileDma<D, NW> dma_kv, dma_st;  // lane offsets for rows of K/V (caller's stride) and of workspace tiles (stride D)
-  dma_kv.init(p.stride_n, wave, lane);
-  if (n_chunks) dma_st.init(D, wave, lane);
-
-  auto stage_exact = [&](const uint16_t* src, int r0, char* lds) {
-    const int valid = n - r0;
-    const uint16_t* base = src + (int64_t)r0 * p.stride_n;
-    if (valid >= 64) dma_kv.template issue<64>(base, p.stride_n, lds, wave);
-    else if (valid >= 1) dma_kv.template issue_clamped<64>(base, p.stride_n, valid, lds, wave, lane);
-    // valid <= 0: the tile does not exist (second half of a short last block); every logit of it is
-    // masked and the stale, finite LDS contents meet zero weights
-  };
-  auto stage_stats = [&](int chunk, char* lds) { dma_st.template issue<64>(st + (int64_t)chunk * 64 * D, D, lds, wave); };
-  auto stage_hg = [&](int g, int half, char* lds) {
-    dma_st.template issue<D / 2>(hg + ((int64_t)g * D + half * (D / 2)) * D, D, lds, wave);
+    return u;
   };
   auto first_group = [&](int chunk) { return (32 * chunk) / p.group; };
   auto last_group = [&](int chunk) { return (min(32 * chunk + 32, p.nb) - 1) / p.group; };
 
-  // ---------------- exact tiles: K in lds_x, V in lds_y ----------------
-  int r0 = key_row0(0);
-  stage_exact(kb, r0, lds_x);
-  wait_dma_and_sync();
-  stage_exact(vb, r0, lds_y);
-  for (int it = 0; it < n_exact; ++it) {
-    const bool more = it + 1 < n_exact;
-    const int r0_next = more ? key_row0(it + 1) : 0;
-    bf16x8 pf[4];
-    exact_tile_scores<D>(lds_x, w, p.c, n - r0, lane, pf);
-    wait_dma_and_sync();  // V tile visible to every wave; every wave is done with the K tile
-    if (more) stage_exact(kb, r0_next, lds_x);
-    else if (n_chunks) stage_stats(0, lds_x);
-    exact_tile_pv<D>(lds_y, w, pf, lane);
-    wait_dma_and_sync();  // next K (or first statistics tile) visible; every wave is done with the V tile
-    if (more) stage_exact(vb, r0_next, lds_y);
-    else if (n_chunks) stage_hg(first_group(0), 0, lds_y);
-    r0 = r0_next;
+  // ---- the producer side: a cursor over the tile stream, advanced once per ring slot ----
+  //   exact phase:   K tile, V tile of every step of the union walk (dense: of every 64 keys)
+  //   approx phase:  per chunk: statistics tile, then the HPARTS tiles of every group it intersects
+  UnionWalk pw = make_walk();
+  int p_dense = 0;                            // dense: next tile
+  int p_side = 0;                             // 0: K next, 1: V next
+  int p_chunk = 0, p_group = 0, p_part = -1;  // approx cursor; p_part == -1: statistics tile next
+  int issued = 0;                             // tiles requested so far
+  bool p_exact_done = false;
+  auto issue_next = [&]() {  // requests the next tile of the stream, if there is one
+    const uint32_t dst = buf_addr(issued);
+    if (!p_exact_done) {
+      const int r0 = SPARSE ? pw.block() * p.block + pw.sub * 64 : p_dense * 64;
+      const uint16_t* src = p_side ? vb : kb;
+      const int valid = n - r0;
+      if (valid >= 64) TileDma<D>::issue(src + (int64_t)r0 * p.stride_n, p.stride_n, dst, wave, lane);
+      else if (valid >= 1) TileDma<D>::issue_clamped(src + (int64_t)r0 * p.stride_n, p.stride_n, valid, dst, wave, lane);
+      else TileDma<D>::issue_clamped(src + (int64_t)(n - 1) * p.stride_n, p.stride_n, 1, dst, wave, lane);
+      if (p_side == 1) {
+        if constexpr (SPARSE) { pw.advance(tiles_per_block); p_exact_done = pw.done(); }
+        else { ++p_dense; p_exact_done = p_dense >= n_dense_tiles; }
+      }
+      p_side ^= 1;
+      ++issued;
+    } else if (p_chunk < n_chunks) {
+      if (p_part < 0) {
+        TileDma<D>::issue(st + (int64_t)p_chunk * 64 * D, D, dst, wave, lane);
+        p_group = first_group(p_chunk);
+        p_part = 0;
+      } else {
+        TileDma<D>::issue(hg + ((int64_t)p_group * D + 64 * p_part) * D, D, dst, wave, lane);
+        if (++p_part == HPARTS) {
+          p_part = 0;
+          if (++p_group > last_group(p_chunk)) { ++p_chunk; p_part = -1; }
+        }
+      }
+      ++issued;
+    }
+  };
+
+  // ---- the consumer side ----
+  int consumed = 0;  // tiles consumed so far == index of the tile being consumed
+  // Before reading tile `consumed`: wait for it, meet the other waves, refill the slot just freed.
+  auto acquire = [&]() {
+    ring_barrier<NI>(issued - consumed - 1);
+    issue_next();
+  };
+
+#pragma unroll 1
+  for (int i = 0; i < kAhead; ++i) issue_next();
+
+  // ---------------- exact tiles ----------------
+  {
+    UnionWalk cw = make_walk();
+    int c_dense = 0;
+    while (SPARSE ? !cw.done() : (c_dense < n_dense_tiles)) {
+      const int r0 = SPARSE ? cw.block() * p.block + cw.sub * 64 : c_dense * 64;
+      const bool mine = !SPARSE || (second ? cw.in_b() : cw.in_a());
+      bf16x8 pf[4];
+      acquire();
+      if (mine) exact_tile_scores<D>(buf(consumed), w, p.c, n - r0, lane, pf);
+      ++consumed;
+      acquire();
+      if (mine) exact_tile_pv<D>(buf(consumed), w, pf, lane);
+      ++consumed;
+      if constexpr (SPARSE) cw.advance(tiles_per_block);
+      else ++c_dense;
+    }
   }
 
   // ---------------- grouped approximation of the unselected blocks ----------------
-  // On entry of a chunk: its statistics tile is visible in `ps`, the first half of its first group
-  // matrix is on its way to `pq`.  The two buffers swap roles from one chunk to the next.
-  auto approx_chunk = [&](int chunk, char* ps, char* pq) {
-    bf16x8 pf[2];
-    f32x16 a;
-    approx_chunk_scores<D>(ps, w, p.c, mask_row[chunk], chunk, p.nb, p.block, p.tail, lane, a, pf);
-    approx_chunk_pv<D>(ps, w, pf, lane);
-    const bool more = chunk + 1 < n_chunks;
+  for (int chunk = 0; chunk < n_chunks; ++chunk) {
+    f32x16 a = {0};
+    acquire();
+    if (qb_exists)
+      approx_chunk_zeroth<D>(buf(consumed), w, p.c, mask_row[chunk], chunk, p.nb, p.block, p.tail, lane, a);
+    ++consumed;
     const int g_last = last_group(chunk);
     for (int g = first_group(chunk); g <= g_last; ++g) {
       float A = 0.f;
@@ -330,26 +406,19 @@ __global__ void __launch_bounds__(NW * 64, 2) attn_kernel(AttnParams p) {
         A += (j / p.group == g) ? a[r] : 0.f;
       }
       A = half_swap_sum(A);
-      wait_dma_and_sync();  // first half of Hg visible in pq; ps is free
-      stage_hg(g, 1, ps);
-      first_order_half<D>(pq, w, A, 0, lane);
-      wait_dma_and_sync();  // second half visible in ps; pq is free
-      if (g < g_last) stage_hg(g + 1, 0, pq);
-      else if (more) stage_stats(chunk + 1, pq);
-      first_order_half<D>(ps, w, A, 1, lane);
+#pragma unroll
+      for (int part = 0; part < HPARTS; ++part) {
+        acquire();
+        if (qb_exists) first_order_part<D>(buf(consumed), w, A, part, lane);
+        ++consumed;
+      }
     }
-    wait_dma_and_sync();  // next statistics tile visible in pq; ps is free
-    if (more) stage_hg(first_group(chunk + 1), 0, ps);
-  };
-  for (int chunk = 0; chunk < n_chunks; chunk += 2) {
-    approx_chunk(chunk, lds_x, lds_y);
-    if (chunk + 1 < n_chunks) approx_chunk(chunk + 1, lds_y, lds_x);
   }
 
   // ---- epilogue: normalise and write ----
   const float l_tot = half_swap_sum(w.l);
   const float inv = 1.0f / l_tot;
-  if (q_row < n) {
+  if (q_row < n && qb_exists) {
     uint16_t* orow = p.o + head_off + (int64_t)q_row * p.stride_n;
 #pragma unroll
     for (int t = 0; t < D / 32; ++t)
@@ -365,9 +434,9 @@ __global__ void __launch_bounds__(NW * 64, 2) attn_kernel(AttnParams p) {
   }
 }
 
-template <int D, int NW, bool SPARSE>
+template <int D, bool SPARSE>
 hipError_t launch(const AttnParams& p, int grid, hipStream_t stream) {
-  hipLaunchKernelGGL((attn_kernel<D, NW, SPARSE>), dim3(grid), dim3(NW * 64), 0, stream, p);
+  hipLaunchKernelGGL((attn_kernel<D, SPARSE>), dim3(grid), dim3(kWaves * 64), 0, stream, p);
   return hipGetLastError();
 }
 
@@ -375,20 +444,15 @@ hipError_t launch(const AttnParams& p, int grid, hipStream_t stream) {
 
 hipError_t pasa_launch_attn(AttnParams p, bool sparse, int d, hipStream_t stream) {
   p.c = p.scale * kLog2e;
+  p.q_tiles = (p.n + 127) / 128;  // 128 query rows per workgroup
+  p.q_tiles_per_xcd = (p.q_tiles + kXcds - 1) / kXcds;
+  const int grid = p.bh * kXcds * p.q_tiles_per_xcd;
   if (sparse) {
-    p.q_tiles = p.nb;  // one workgroup per query block
-    p.q_tiles_per_xcd = (p.q_tiles + kXcds - 1) / kXcds;
-    const int grid = p.bh * kXcds * p.q_tiles_per_xcd;
-    if (d == 128 && p.block == 64) return launch<128, 2, true>(p, grid, stream);
-    if (d == 128 && p.block == 128) return launch<128, 4, true>(p, grid, stream);
-    if (d == 64 && p.block == 64) return launch<64, 2, true>(p, grid, stream);
-    if (d == 64 && p.block == 128) return launch<64, 4, true>(p, grid, stream);
+    if (d == 128) return launch<128, true>(p, grid, stream);
+    if (d == 64) return launch<64, true>(p, grid, stream);
   } else {
-    p.q_tiles = (p.n + 127) / 128;
-    p.q_tiles_per_xcd = (p.q_tiles + kXcds - 1) / kXcds;
-    const int grid = p.bh * kXcds * p.q_tiles_per_xcd;
-    if (d == 128) return launch<128, 4, false>(p, grid, stream);
-    if (d == 64) return launch<64, 4, false>(p, grid, stream);
+    if (d == 128) return launch<128, false>(p, grid, stream);
+    if (d == 64) return launch<64, false>(p, grid, stream);
   }
   return hipErrorInvalidValue;
 }
