@@ -60,6 +60,12 @@ typedef struct {
                     Ignored by pasa_block_score and pasa_attn_dense_ref.                          */
   int64_t stride_b, stride_h, stride_n; /* element strides of Q, K, V and O; d is contiguous     */
   float scale; /* logit scale; 0 means 1/sqrt(d) (Eq.1)                                          */
+  int32_t kv_slices; /* tuning knob of pasa_sparse_attn_fwd: the key range is cut into this many
+                    contiguous slices, slice s is walked by workgroups of XCD s % 8 only (so that a
+                    slice of K and V stays resident in that XCD's L2) and the per-slice partial results
+                    are merged by a second kernel.  0 = the library chooses; 1 = no slicing; otherwise
+                    a multiple of 8 not above ceil(N_B / 32).  Results do not depend on it beyond
+                    floating-point summation order.                                               */
 } pasa_shape_t;
 
 /* host-only. */
@@ -137,7 +143,7 @@ PASA_API int pasa_kv_stats(const void* k, const void* v, const pasa_shape_t* sha
  * attention kernel).  pasa_sparse_attn_fwd_prepared runs the attention kernel alone and requires
  * that `ws` was filled by pasa_kv_stats for the same k, v and shape and not touched since.
  *   idx    int32 [BH, N_B, k_sel], each row strictly ascending, values in [0, N_B) (not checked)
- *   mask   the bitmap pasa_route wrote for the same idx (required unless shape->group == 0)
+ *   mask   the bitmap pasa_route wrote for the same idx
  *   out    bf16 [B,H,n,d] (shape strides)
  *   lse    fp32 [BH, n] or NULL: log(Den) including the subtracted maximum
  *   ws     scratch of pasa_attn_workspace_bytes(shape) bytes, 256-byte aligned

@@ -37,24 +37,50 @@ int check_group(int group, int nb) {
 float effective_scale(const pasa_shape_t* s) { return s->scale > 0.f ? s->scale : 1.0f / sqrtf((float)s->d); }
 
 struct AttnWorkspace {
-  size_t st, hg, partial, total;
-  int n_groups, unit, n_units, n_chunks;
+  size_t st, hg, partial, part_o, part_ml, total;
+  int n_groups, unit, n_units, n_chunks, n_slices;
 };
+
+// Number of key-range slices of the sparse kernel.  K and V of one head should fit the 4 MB L2 of an
+// XCD slice by slice; there are 8 XCDs, so slices come in multiples of 8.
+int choose_slices(const pasa_shape_t* s) {
+  const int n_chunks = (num_blocks(s) + 31) / 32;
+  if (s->kv_slices == 1) return 1;
+  if (s->kv_slices > 1) return s->kv_slices;
+  const size_t kv_bytes = (size_t)s->n * s->d * 2 * 2;
+  if (kv_bytes <= ((size_t)4 << 20) || n_chunks < 8) return 1;
+  int rounds = (int)((kv_bytes + ((size_t)40 << 20) - 1) / ((size_t)40 << 20));  // <= 5 MB per slice
+  while (rounds > 1 && 8 * rounds > n_chunks) --rounds;
+  return 8 * rounds;
+}
+
+int check_slices(const pasa_shape_t* s) {
+  if (s->kv_slices < 0) return PASA_EINVAL;
+  if (s->kv_slices <= 1) return PASA_OK;
+  if (s->kv_slices % 8 != 0 || s->kv_slices > (num_blocks(s) + 31) / 32) return PASA_EUNSUPPORTED;
+  return PASA_OK;
+}
 
 AttnWorkspace carve_attn(const pasa_shape_t* s) {
   AttnWorkspace w{};
   const int nb = num_blocks(s);
   const size_t bh = (size_t)s->B * s->H;
-  if (s->group <= 0) return w;  // no statistics needed
-  const int group = s->group >= nb ? nb : s->group;
-  w.n_groups = (nb + group - 1) / group;
-  w.unit = group < 32 ? group : 32;
-  w.n_units = (nb + w.unit - 1) / w.unit;
   w.n_chunks = (nb + 31) / 32;
+  w.n_slices = choose_slices(s);
   size_t off = 0;
-  w.st = off; off = align_up(off + bh * w.n_chunks * 64 * s->d * 2);
-  w.hg = off; off = align_up(off + bh * w.n_groups * s->d * s->d * 2);
-  w.partial = off; off = align_up(off + bh * w.n_units * s->d * s->d * 4);
+  if (w.n_slices > 1) {
+    w.part_o = off; off = align_up(off + bh * w.n_slices * s->n * s->d * 4);
+    w.part_ml = off; off = align_up(off + bh * w.n_slices * s->n * 2 * 4);
+  }
+  if (s->group > 0) {
+    const int group = s->group >= nb ? nb : s->group;
+    w.n_groups = (nb + group - 1) / group;
+    w.unit = group < 32 ? group : 32;
+    w.n_units = (nb + w.unit - 1) / w.unit;
+    w.st = off; off = align_up(off + bh * w.n_chunks * 64 * s->d * 2);
+    w.hg = off; off = align_up(off + bh * w.n_groups * s->d * s->d * 2);
+    w.partial = off; off = align_up(off + bh * w.n_units * s->d * s->d * 4);
+  }
   w.total = off;
   return w;
 }
@@ -99,6 +125,7 @@ size_t pasa_score_workspace_bytes(const pasa_shape_t* shape) {
 size_t pasa_attn_workspace_bytes(const pasa_shape_t* shape) {
   if (check_shape(shape) != PASA_OK) return 0;
   if (check_group(shape->group, num_blocks(shape)) != PASA_OK) return 0;
+  if (check_slices(shape) != PASA_OK) return 0;
   const size_t t = carve_attn(shape).total;
   return t ? t : kAlign;  // never zero for a valid shape, so that 0 always means "bad shape"
 }
@@ -144,9 +171,11 @@ static int check_attn_args(const pasa_shape_t* shape, bool sparse, const void* w
   const int rc = check_shape(shape);
   if (rc != PASA_OK) return rc;
   *s = *shape;
-  if (!sparse) s->group = 0;
+  if (!sparse) { s->group = 0; s->kv_slices = 1; }
   const int rg = check_group(s->group, num_blocks(s));
   if (rg != PASA_OK) return rg;
+  const int rs = check_slices(s);
+  if (rs != PASA_OK) return rs;
   if (!ws) return PASA_EINVAL;
   if (!aligned16(ws)) return PASA_EALIGN;
   if (ws_bytes < pasa_attn_workspace_bytes(s)) return PASA_EWORKSPACE;
@@ -187,8 +216,7 @@ static int attn_common(const void* q, const void* k, const void* v, const pasa_s
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return PASA_EALIGN;
   if (out == q || out == k || out == v) return PASA_EINVAL;
   if (sparse) {
-    if (!idx || k_sel < 1 || k_sel > nb) return PASA_EINVAL;
-    if (s.group > 0 && !mask) return PASA_EINVAL;
+    if (!idx || !mask || k_sel < 1 || k_sel > nb) return PASA_EINVAL;
   }
   if (sparse && with_stats) {
     const int rs = pasa_kv_stats(k, v, &s, ws, ws_bytes, stream);
@@ -202,6 +230,7 @@ static int attn_common(const void* q, const void* k, const void* v, const pasa_s
   a.stride_b = s.stride_b; a.stride_h = s.stride_h; a.stride_n = s.stride_n;
   a.bh = s.B * s.H; a.H = s.H; a.n = s.n; a.nb = nb; a.block = s.block; a.tail = s.n - (nb - 1) * s.block;
   a.scale = effective_scale(&s);
+  a.n_slices = 1;
   if (sparse) {
     a.idx = idx; a.mask = mask; a.k_sel = k_sel; a.mask_words = (nb + 31) / 32;
     a.group = s.group >= nb ? nb : s.group;
@@ -209,6 +238,9 @@ static int attn_common(const void* q, const void* k, const void* v, const pasa_s
     a.hg = reinterpret_cast<const uint16_t*>(base + w.hg);
     a.n_groups = w.n_groups;
     a.n_chunks = w.n_chunks;
+    a.n_slices = w.n_slices;
+    a.part_o = reinterpret_cast<float*>(base + w.part_o);
+    a.part_ml = reinterpret_cast<float*>(base + w.part_ml);
   }
   return pasa_launch_attn(a, sparse, s.d, static_cast<hipStream_t>(stream)) == hipSuccess ? PASA_OK : PASA_EHIP;
 }

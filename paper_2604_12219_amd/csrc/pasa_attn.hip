@@ -17,11 +17,20 @@
 // wave pair computes on it only if its own list contains the block.  Adjacent query blocks of a
 // video select heavily overlapping key blocks, so this cuts the K/V traffic per query block.
 //
+// Key-range slicing (sparse path, long sequences).  L2 misses of all XCDs share one fabric whose read
+// bandwidth is far below what the eight L2s deliver on hits, and one head's K and V are much larger
+// than one L2.  So the key range is cut into slices that fit an L2; workgroups whose id is congruent
+// to x modulo 8 run on XCD x and walk only slice x (+8, +16, ...) of every query tile.  Each slice of
+// K and V is then fetched from memory once per head and XCD and hit in L2 afterwards.  Every
+// workgroup leaves an unnormalised partial result (running maximum, normaliser share, numerator),
+// and a small second kernel merges the partial results of a row.
+//
 // Data movement.  All tiles (K, V, block statistics, group matrices) are 64-row tiles that stream
 // through a ring of four LDS buffers by direct global->LDS loads, requested three tiles ahead of
 // their use; one workgroup barrier per tile.
 #include "pasa_device.hpp"
 #include "pasa_kernels.hpp"
+#include <stdlib.h>
 
 namespace {
 
@@ -32,6 +41,11 @@ constexpr int kWaves = 4;   // waves per workgroup
 constexpr int kRing = 4;    // LDS tile buffers
 constexpr int kAhead = 3;   // a tile is requested this many tiles before it is consumed
 constexpr int kNoBlock = 0x7fffffff;
+#ifdef PASA_DEBUG_MODES
+constexpr bool kDebugModes = true;   // timing experiments: results are wrong on purpose
+#else
+constexpr bool kDebugModes = false;
+#endif
 
 typedef __attribute__((address_space(4))) const int32_t const_i32;
 typedef __attribute__((address_space(4))) const uint32_t const_u32;
@@ -265,12 +279,22 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int ql = lane & 31, h = lane >> 5;
-  // Workgroup -> (head, query tile).  The hardware deals consecutive workgroup ids round-robin to
-  // the 8 XCDs, so ids are decoded such that one XCD owns a contiguous run of query tiles of one
-  // head and all XCDs work on the same head at the same time.
+  // Workgroup -> (head, query tile[, key slice]).  The hardware deals consecutive workgroup ids
+  // round-robin to the 8 XCDs.  Without slicing, ids are decoded such that one XCD owns a contiguous
+  // run of query tiles of one head and all XCDs work on the same head at the same time.
   const int xcd = blockIdx.x % kXcds, local = blockIdx.x / kXcds;
-  const int bh = local / p.q_tiles_per_xcd, qt = xcd * p.q_tiles_per_xcd + local % p.q_tiles_per_xcd;
-  if (qt >= p.q_tiles) return;  // padding workgroup (the whole workgroup leaves before any barrier)
+  int bh, qt, slice = 0;
+  if (p.n_slices > 1) {  // (head, round, query tile) x XCD; XCD x walks slice x + 8 * round
+    const int rounds = p.n_slices / kXcds;
+    qt = local % p.q_tiles;
+    const int hr = local / p.q_tiles;
+    slice = (hr % rounds) * kXcds + xcd;
+    bh = hr / rounds;
+  } else {
+    bh = local / p.q_tiles_per_xcd;
+    qt = xcd * p.q_tiles_per_xcd + local % p.q_tiles_per_xcd;
+    if (qt >= p.q_tiles) return;  // padding workgroup (the whole workgroup leaves before any barrier)
+  }
   const int64_t head_off = (int64_t)(bh / p.H) * p.stride_b + (int64_t)(bh % p.H) * p.stride_h;
   const uint16_t* const qb = p.q + head_off;
   const uint16_t* const kb = p.k + head_off;
@@ -300,18 +324,42 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
   const bool qb_exists = !SPARSE || my_qb < p.nb;         // the second block of the last pair may not exist
   const int tiles_per_block = SPARSE ? p.block / 64 : 1;
   const int n_dense_tiles = (n + 63) / 64;
-  const int n_chunks = (SPARSE && p.group > 0) ? p.n_chunks : 0;
-  const uint16_t* const st = n_chunks ? p.st + (int64_t)bh * p.n_chunks * 64 * D : nullptr;
-  const uint16_t* const hg = n_chunks ? p.hg + (int64_t)bh * p.n_groups * D * D : nullptr;
+  const bool approx_on = SPARSE && p.group > 0;
+  const uint16_t* const st = approx_on ? p.st + (int64_t)bh * p.n_chunks * 64 * D : nullptr;
+  const uint16_t* const hg = approx_on ? p.hg + (int64_t)bh * p.n_groups * D * D : nullptr;
   const_u32* const mask_row =
-      (n_chunks && qb_exists) ? (const_u32*)(p.mask + ((int64_t)bh * p.nb + my_qb) * p.mask_words) : nullptr;
+      (approx_on && qb_exists) ? (const_u32*)(p.mask + ((int64_t)bh * p.nb + my_qb) * p.mask_words) : nullptr;
 
+  // chunk range of this workgroup's slice, and for each list the entries that fall into it: their
+  // number and the position of the first one are popcounts over the selection bitmap
+  const int c_lo = SPARSE ? (int)((int64_t)slice * p.n_chunks / p.n_slices) : 0;
+  const int c_hi = SPARSE ? (int)((int64_t)(slice + 1) * p.n_chunks / p.n_slices) : 0;
+  int first_a = 0, count_a = SPARSE ? p.k_sel : 0, first_b = 0, count_b = 0;
+  if constexpr (SPARSE) {
+    const bool has_b = qpw == 2 && qt * 2 + 1 < p.nb;
+    count_b = has_b ? p.k_sel : 0;
+    if (p.n_slices > 1) {
+      auto bits_in = [&](const uint32_t* row, int w0, int w1) -> int {  // wave-uniform result
+        int acc = 0;
+        for (int x = w0 + lane; x < w1; x += 64) acc += __popc(row[x]);
+#pragma unroll
+        for (int sh = 32; sh >= 1; sh >>= 1) acc += __shfl_xor(acc, sh);
+        return __builtin_amdgcn_readfirstlane(acc);
+      };
+      const uint32_t* ma = p.mask + ((int64_t)bh * p.nb + (int64_t)qt * qpw) * p.mask_words;
+      first_a = bits_in(ma, 0, c_lo);
+      count_a = bits_in(ma, c_lo, c_hi);
+      if (has_b) {
+        first_b = bits_in(ma + p.mask_words, 0, c_lo);
+        count_b = bits_in(ma + p.mask_words, c_lo, c_hi);
+      }
+    }
+  }
   auto make_walk = [&]() {
     UnionWalk u;
     if constexpr (SPARSE) {
       const_i32* base = (const_i32*)(p.idx + ((int64_t)bh * p.nb + (int64_t)qt * qpw) * p.k_sel);
-      const bool has_b = qpw == 2 && qt * 2 + 1 < p.nb;
-      u.init(base, p.k_sel, base + p.k_sel, has_b ? p.k_sel : 0);
+      u.init(base + first_a, count_a, base + p.k_sel + first_b, count_b);
     } else {
       u.init(nullptr, 0, nullptr, 0);
     }
@@ -326,10 +374,12 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
   UnionWalk pw = make_walk();
   int p_dense = 0;                            // dense: next tile
   int p_side = 0;                             // 0: K next, 1: V next
-  int p_chunk = 0, p_group = 0, p_part = -1;  // approx cursor; p_part == -1: statistics tile next
+  const int c_end = approx_on ? c_hi : 0;     // chunks [c_lo, c_end) are approximated by this workgroup
+  int p_chunk = c_lo, p_group = 0, p_part = -1;  // approx cursor; p_part == -1: statistics tile next
   int issued = 0;                             // tiles requested so far
-  bool p_exact_done = false;
+  bool p_exact_done = SPARSE ? pw.done() : false;  // a slice may hold no selected block at all
   auto issue_next = [&]() {  // requests the next tile of the stream, if there is one
+    if (kDebugModes && p.debug_mode == 1 && issued >= kAhead) return;
     const uint32_t dst = buf_addr(issued);
     if (!p_exact_done) {
       const int r0 = SPARSE ? pw.block() * p.block + pw.sub * 64 : p_dense * 64;
@@ -344,7 +394,7 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
       }
       p_side ^= 1;
       ++issued;
-    } else if (p_chunk < n_chunks) {
+    } else if (p_chunk < c_end) {
       if (p_part < 0) {
         TileDma<D>::issue(st + (int64_t)p_chunk * 64 * D, D, dst, wave, lane);
         p_group = first_group(p_chunk);
@@ -380,10 +430,10 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
       const bool mine = !SPARSE || (second ? cw.in_b() : cw.in_a());
       bf16x8 pf[4];
       acquire();
-      if (mine) exact_tile_scores<D>(buf(consumed), w, p.c, n - r0, lane, pf);
+      if (mine && !(kDebugModes && p.debug_mode == 2)) exact_tile_scores<D>(buf(consumed), w, p.c, n - r0, lane, pf);
       ++consumed;
       acquire();
-      if (mine) exact_tile_pv<D>(buf(consumed), w, pf, lane);
+      if (mine && !(kDebugModes && p.debug_mode == 2)) exact_tile_pv<D>(buf(consumed), w, pf, lane);
       ++consumed;
       if constexpr (SPARSE) cw.advance(tiles_per_block);
       else ++c_dense;
@@ -391,7 +441,7 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
   }
 
   // ---------------- grouped approximation of the unselected blocks ----------------
-  for (int chunk = 0; chunk < n_chunks; ++chunk) {
+  for (int chunk = c_lo; chunk < c_end; ++chunk) {
     f32x16 a = {0};
     acquire();
     if (qb_exists)
@@ -415,23 +465,75 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
     }
   }
 
-  // ---- epilogue: normalise and write ----
+  // ---- epilogue ----
   const float l_tot = half_swap_sum(w.l);
-  const float inv = 1.0f / l_tot;
-  if (q_row < n && qb_exists) {
-    uint16_t* orow = p.o + head_off + (int64_t)q_row * p.stride_n;
+  if (!(q_row < n && qb_exists)) return;
+  if (p.n_slices > 1) {  // leave the partial result of this slice to the merge kernel
+    const int64_t prow = ((int64_t)bh * p.n_slices + slice) * n + q_row;
+    float* orow = p.part_o + prow * D;
 #pragma unroll
     for (int t = 0; t < D / 32; ++t)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-        bf16x4 ov;
+        typedef float f32x4 __attribute__((ext_vector_type(4)));
+        f32x4 ov;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) ov[r] = (__bf16)(w.o[t][4 * g + r] * inv);
-        *reinterpret_cast<bf16x4*>(orow + 32 * t + 8 * g + 4 * h) = ov;
+        for (int r = 0; r < 4; ++r) ov[r] = w.o[t][4 * g + r];
+        __builtin_nontemporal_store(ov, reinterpret_cast<f32x4*>(orow + 32 * t + 8 * g + 4 * h));
       }
-    if (p.lse && h == 0) p.lse[(int64_t)bh * n + q_row] = (w.m + __builtin_amdgcn_logf(l_tot)) * kLn2;
+    if (h == 0) {
+      typedef float f32x2 __attribute__((ext_vector_type(2)));
+      f32x2 ml = {w.m, l_tot};
+      __builtin_nontemporal_store(ml, reinterpret_cast<f32x2*>(p.part_ml + prow * 2));
+    }
+    return;
   }
+  const float inv = 1.0f / l_tot;
+  uint16_t* orow = p.o + head_off + (int64_t)q_row * p.stride_n;
+#pragma unroll
+  for (int t = 0; t < D / 32; ++t)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+      bf16x4 ov;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) ov[r] = (__bf16)(w.o[t][4 * g + r] * inv);
+      *reinterpret_cast<bf16x4*>(orow + 32 * t + 8 * g + 4 * h) = ov;
+    }
+  if (p.lse && h == 0) p.lse[(int64_t)bh * n + q_row] = (w.m + __builtin_amdgcn_logf(l_tot)) * kLn2;
+}
+
+// Merge of the per-slice partial results of a row:  M = max_s m_s,  w_s = 2^(m_s - M),
+//   O = sum_s w_s Num_s / sum_s w_s l_s.   A slice that saw nothing has m_s = -inf, l_s = 0.
+// One thread owns 4 value columns of one row; 32 (D = 128) or 16 (D = 64) threads per row.
+template <int D>
+__global__ void __launch_bounds__(256) merge_kernel(AttnParams p) {
+  constexpr int TPR = D / 4;
+  const int64_t row = (int64_t)blockIdx.x * (256 / TPR) + threadIdx.x / TPR;  // flat (bh, token)
+  if (row >= (int64_t)p.bh * p.n) return;
+  const int c4 = threadIdx.x % TPR;
+  const int bh = (int)(row / p.n), tok = (int)(row % p.n);
+  const int64_t prow0 = (int64_t)bh * p.n_slices * p.n + tok;
+  float M = -INFINITY;
+  for (int s = 0; s < p.n_slices; ++s) M = fmaxf(M, p.part_ml[(prow0 + (int64_t)s * p.n) * 2]);
+  float L = 0.f, acc[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < p.n_slices; ++s) {
+    const int64_t pr = prow0 + (int64_t)s * p.n;
+    const float ws = __builtin_amdgcn_exp2f(p.part_ml[pr * 2] - M);
+    L += ws * p.part_ml[pr * 2 + 1];
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p.part_o + pr * D + 4 * c4));
+#pragma unroll
+    for (int r = 0; r < 4; ++r) acc[r] += ws * v[r];
+  }
+  const float inv = 1.0f / L;
+  typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+  bf16x4 ov;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) ov[r] = (__bf16)(acc[r] * inv);
+  const int64_t head_off = (int64_t)(bh / p.H) * p.stride_b + (int64_t)(bh % p.H) * p.stride_h;
+  *reinterpret_cast<bf16x4*>(p.o + head_off + (int64_t)tok * p.stride_n + 4 * c4) = ov;
+  if (p.lse && c4 == 0) p.lse[row] = (M + __builtin_amdgcn_logf(L)) * kLn2;
 }
 
 template <int D, bool SPARSE>
@@ -444,15 +546,25 @@ hipError_t launch(const AttnParams& p, int grid, hipStream_t stream) {
 
 hipError_t pasa_launch_attn(AttnParams p, bool sparse, int d, hipStream_t stream) {
   p.c = p.scale * kLog2e;
+  p.debug_mode = 0;
+#ifdef PASA_DEBUG_MODES
+  if (const char* e = getenv("PASA_DEBUG_MODE")) p.debug_mode = atoi(e);
+#endif
   p.q_tiles = (p.n + 127) / 128;  // 128 query rows per workgroup
   p.q_tiles_per_xcd = (p.q_tiles + kXcds - 1) / kXcds;
-  const int grid = p.bh * kXcds * p.q_tiles_per_xcd;
-  if (sparse) {
-    if (d == 128) return launch<128, true>(p, grid, stream);
-    if (d == 64) return launch<64, true>(p, grid, stream);
+  if (!sparse) p.n_slices = 1;
+  const int grid = p.n_slices > 1 ? p.bh * p.n_slices * p.q_tiles : p.bh * kXcds * p.q_tiles_per_xcd;
+  hipError_t rc = hipErrorInvalidValue;
+  if (sparse && d == 128) rc = launch<128, true>(p, grid, stream);
+  else if (sparse && d == 64) rc = launch<64, true>(p, grid, stream);
+  else if (d == 128) rc = launch<128, false>(p, grid, stream);
+  else if (d == 64) rc = launch<64, false>(p, grid, stream);
+  if (rc != hipSuccess || p.n_slices == 1) return rc;
+  const int64_t rows = (int64_t)p.bh * p.n;
+  if (d == 128) {
+    hipLaunchKernelGGL(merge_kernel<128>, dim3((unsigned)((rows + 7) / 8)), dim3(256), 0, stream, p);
   } else {
-    if (d == 128) return launch<128, false>(p, grid, stream);
-    if (d == 64) return launch<64, false>(p, grid, stream);
+    hipLaunchKernelGGL(merge_kernel<64>, dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, stream, p);
   }
-  return hipErrorInvalidValue;
+  return hipGetLastError();
 }

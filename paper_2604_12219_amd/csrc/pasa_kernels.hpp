@@ -14,6 +14,7 @@ struct AttnParams {
   int64_t stride_b, stride_h, stride_n;
   int32_t bh, H, n, nb, block, tail;  // tail = valid tokens of the last block
   float scale, c;                     // c = scale * log2(e), filled in by the launcher
+  int32_t debug_mode;                 // experiments only (PASA_DEBUG_MODES builds): 1 = no tile loads, 2 = no math
   int32_t q_tiles, q_tiles_per_xcd;   // filled in by the launcher
   // sparse path only
   const int32_t* idx;
@@ -23,6 +24,10 @@ struct AttnParams {
                          // sums of key blocks 32c..32c+31 (zero rows for blocks that do not exist)
   const uint16_t* hg;    // bf16 [BH][n_groups][d][d]: (scale * Hg)^T, row = value column, col = key column
   int32_t group, n_groups, n_chunks;
+  // key-range slicing (sparse path): slice s covers chunks [s*n_chunks/n_slices, (s+1)*n_chunks/n_slices)
+  int32_t n_slices;      // 1 = off (the attention kernel writes the output itself)
+  float* part_o;         // fp32 [BH][n_slices][n][d]: unnormalised partial numerators
+  float* part_ml;        // fp32 [BH][n_slices][n][2]: running maximum (log2 units) and partial normaliser
 };
 
 // dense (sparse = false) or piecewise sparse attention; d in {64,128}, block in {64,128}

@@ -31,7 +31,7 @@ class _CShape(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("n", ctypes.c_int32), ("d", ctypes.c_int32),
                 ("block", ctypes.c_int32), ("group", ctypes.c_int32),
                 ("stride_b", ctypes.c_int64), ("stride_h", ctypes.c_int64), ("stride_n", ctypes.c_int64),
-                ("scale", ctypes.c_float)]
+                ("scale", ctypes.c_float), ("kv_slices", ctypes.c_int32)]
 
 
 @dataclass
@@ -46,17 +46,18 @@ class Shape:
     stride_h: int = 0
     stride_n: int = 0
     scale: float = 0.0
+    kv_slices: int = 0
 
     @staticmethod
-    def of(x: torch.Tensor, block: int = 64, group: int = 32, scale: float = 0.0) -> "Shape":
+    def of(x: torch.Tensor, block: int = 64, group: int = 32, scale: float = 0.0, kv_slices: int = 0) -> "Shape":
         if x.dim() != 4 or x.stride(3) != 1:
             raise ValueError("expected a [B, H, n, d] tensor with contiguous last dimension")
         B, H, n, d = x.shape
-        return Shape(B, H, n, d, block, group, x.stride(0), x.stride(1), x.stride(2), scale)
+        return Shape(B, H, n, d, block, group, x.stride(0), x.stride(1), x.stride(2), scale, kv_slices)
 
     def c(self) -> _CShape:
         return _CShape(self.B, self.H, self.n, self.d, self.block, self.group, self.stride_b, self.stride_h,
-                       self.stride_n, self.scale)
+                       self.stride_n, self.scale, self.kv_slices)
 
 
 def lib_path() -> str:

@@ -112,8 +112,8 @@ def test_routing_on_real_scores_and_determinism(P):
 # ------------------------------------------------------------------------------------------------
 # stages 3+4: piecewise attention
 # ------------------------------------------------------------------------------------------------
-def _run_sparse(P, q, k, v, block, group, keep, seed=3, amp=0.3):
-    shape = P.Shape.of(q, block=block, group=group)
+def _run_sparse(P, q, k, v, block, group, keep, seed=3, amp=0.3, kv_slices=0):
+    shape = P.Shape.of(q, block=block, group=group, kv_slices=kv_slices)
     nb = P.num_blocks(shape)
     k_sel = P.topk_count(nb, keep)
     scores = P.block_score(q, k, shape)
@@ -146,6 +146,33 @@ def test_sparse_matches_oracle(P, grid, heads, d, block, group, keep):
     res = oracle.pasa_attention(to_f64(q), to_f64(k), to_f64(v), idx.cpu().numpy(), block, group=group,
                                 return_all=True)
     assert_close(to_f64(out), res["o"], what=f"sparse {grid} d={d} b={block} G={group}")
+    np.testing.assert_allclose(lse.cpu().numpy(), res["lse"], atol=2e-2)
+
+
+SLICED_CASES = [
+    # grid, d, block, group, keep, kv_slices   (needs at least kv_slices chunks of 32 key blocks)
+    ((8, 45, 46), 128, 64, 32, 0.15, 8),    # n=16,560: 259 blocks (tail 48), 9 chunks over 8 slices
+    ((8, 45, 46), 128, 64, 0, 0.02, 8),     # approximation off, very sparse: some slices hold no selected block
+    ((12, 40, 46), 64, 64, 32, 0.1, 8),     # d = 64
+    ((16, 40, 52), 128, 64, 32, 0.05, 16),  # n=33,280: 520 blocks, 17 chunks over 16 slices (two rounds per XCD)
+    ((16, 40, 52), 128, 128, 32, 0.1, 8),   # block 128: 260 blocks, 9 chunks
+]
+
+
+@pytest.mark.parametrize("grid,d,block,group,keep,kv_slices", SLICED_CASES)
+def test_key_range_slicing_matches_oracle_and_unsliced_kernel(P, grid, d, block, group, keep, kv_slices):
+    q, k, v = _inputs(grid, 1, d, seed=13)
+    out, lse, idx = _run_sparse(P, q, k, v, block, group, keep, kv_slices=kv_slices)
+    out1, lse1, idx1 = _run_sparse(P, q, k, v, block, group, keep, kv_slices=1)
+    assert torch.equal(idx, idx1)
+    # same arithmetic up to summation order and one bf16 rounding
+    a, b = out.float(), out1.float()
+    assert (a - b).abs().max().item() <= 2e-2 * b.abs().max().item()
+    assert (a - b).abs().mean().item() <= 1e-3 * b.abs().mean().item()
+    np.testing.assert_allclose(lse.cpu().numpy(), lse1.cpu().numpy(), atol=1e-3)
+    res = oracle.pasa_attention(to_f64(q), to_f64(k), to_f64(v), idx.cpu().numpy(), block, group=group,
+                                return_all=True)
+    assert_close(to_f64(out), res["o"], what=f"sliced {grid} d={d} b={block} G={group} S={kv_slices}")
     np.testing.assert_allclose(lse.cpu().numpy(), res["lse"], atol=2e-2)
 
 
