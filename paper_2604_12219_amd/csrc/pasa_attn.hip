@@ -58,6 +58,42 @@ struct WaveState {
   float l;             // this lane's share of the running normaliser
 };
 
+// Per-lane byte offsets of the MFMA operand fetches inside a 64-row LDS tile, computed once: the XOR
+// swizzle makes them lane-dependent, but a multiple of 16 rows added to the first row does not
+// change the swizzle, so these few registers serve every tile kind through immediate offsets.
+typedef __attribute__((address_space(3))) const bf16x8 lds_bf16x8;
+template <int D>
+struct LaneOffsets {
+  uint32_t k[D / 16];     // row fragment of rows 0..31, step s
+  uint32_t v[D / 32][2];  // column fragment of rows 0..15, value-column tile t; [1]: the rows 8 further down
+  PASA_DEVICE void init(int lane) {
+    const int i = lane & 15, half16 = (lane >> 4) & 1, h = lane >> 5;
+#pragma unroll
+    for (int s = 0; s < D / 16; ++s) k[s] = (uint32_t)lds_chunk_off<D>(lane & 31, 2 * s + h);
+#pragma unroll
+    for (int t = 0; t < D / 32; ++t) {
+      const int row = 4 * h + (i >> 2), col = 32 * t + 16 * half16 + 4 * (i & 3);
+      v[t][0] = (uint32_t)(lds_chunk_off<D>(row, col >> 3) + (col & 7) * 2);
+      v[t][1] = (uint32_t)(lds_chunk_off<D>(row + 8, col >> 3) + (col & 7) * 2);
+    }
+  }
+};
+
+// row fragment (see row_frag): rows row0 .. row0+31 of the tile at LDS address `tile`; row0 in {0, 32}
+template <int D>
+PASA_DEVICE bf16x8 row_frag_at(uint32_t tile, const LaneOffsets<D>& lo, int row0, int s) {
+  return *(lds_bf16x8*)(uintptr_t)(tile + lo.k[s] + (uint32_t)(row0 * 2 * D));
+}
+// column fragment (see col_frag): rows row0 .. row0+15 (row0 a multiple of 16), value columns 32t .. 32t+31
+template <int D>
+PASA_DEVICE bf16x8 col_frag_at(uint32_t tile, const LaneOffsets<D>& lo, int row0, int t) {
+  const uint32_t base = tile + (uint32_t)(row0 * 2 * D);
+  s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(base + lo.v[t][0]));
+  s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(base + lo.v[t][1]));
+  s16x8 v = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
 // Raise the running maximum of a lane to m_new and rescale its accumulators.  Called only when some
 // lane of the wave needs it (the branch around it is wave-uniform).
 template <int D>
@@ -74,14 +110,14 @@ PASA_DEVICE void rescale(WaveState<D>& w, float m_new) {
 // One 64-key tile: logits, online softmax, P^T fragments.  n_valid = number of valid keys (rows) in
 // the tile, may be <= 0 (nothing valid) or >= 64 (all valid).
 template <int D>
-PASA_DEVICE void exact_tile_scores(const char* k_lds, WaveState<D>& w, float c, int n_valid, int lane,
-                                   bf16x8 (&pf)[4]) {
+PASA_DEVICE void exact_tile_scores(uint32_t tile, const LaneOffsets<D>& lo, WaveState<D>& w, float c, int n_valid,
+                                   int lane, bf16x8 (&pf)[4]) {
   const int h = lane >> 5;
   f32x16 s0 = {0}, s1 = {0};
 #pragma unroll
   for (int s = 0; s < D / 16; ++s) {
-    s0 = mfma32(row_frag<D>(k_lds, 0, s, lane), w.qf[s], s0);
-    s1 = mfma32(row_frag<D>(k_lds, 32, s, lane), w.qf[s], s1);
+    s0 = mfma32(row_frag_at<D>(tile, lo, 0, s), w.qf[s], s0);
+    s1 = mfma32(row_frag_at<D>(tile, lo, 32, s), w.qf[s], s1);
   }
   if (n_valid < 64) {
 #pragma unroll
@@ -115,11 +151,13 @@ PASA_DEVICE void exact_tile_scores(const char* k_lds, WaveState<D>& w, float c, 
 }
 
 template <int D>
-PASA_DEVICE void exact_tile_pv(const char* v_lds, WaveState<D>& w, const bf16x8 (&pf)[4], int lane) {
+PASA_DEVICE void exact_tile_pv(uint32_t tile, const LaneOffsets<D>& lo, WaveState<D>& w, const bf16x8 (&pf)[4]) {
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks)  // 16 keys per step: rows 16*ks ..
+  for (int ks = 0; ks < 4; ++ks) {  // 16 keys per step: rows 16*ks ..
 #pragma unroll
-    for (int t = 0; t < D / 32; ++t) w.o[t] = mfma32(col_frag<D>(v_lds, 16 * ks, 32 * t, lane), pf[ks], w.o[t]);
+    for (int t = 0; t < D / 32; ++t) w.o[t] = mfma32(col_frag_at<D>(tile, lo, 16 * ks, t), pf[ks], w.o[t]);
+    if (ks & 1) __builtin_amdgcn_sched_barrier(0);  // keep the operand fetches of at most two steps in flight
+  }
 }
 
 // Zeroth-order part of one chunk of 32 key blocks (Eq.4).  Rows 0..31 of the statistics tile hold
@@ -127,12 +165,12 @@ PASA_DEVICE void exact_tile_pv(const char* v_lds, WaveState<D>& w, const bf16x8 
 // 32*chunk + x is selected; blocks at or beyond nb do not exist.  On return a[r] = a_j of the block
 // in register r (0 for selected or absent blocks).
 template <int D>
-PASA_DEVICE void approx_chunk_zeroth(const char* st_lds, WaveState<D>& w, float c, uint32_t word, int chunk, int nb,
-                                     int block, int tail, int lane, f32x16& a) {
+PASA_DEVICE void approx_chunk_zeroth(uint32_t tile, const LaneOffsets<D>& lo, WaveState<D>& w, float c, uint32_t word,
+                                     int chunk, int nb, int block, int tail, int lane, f32x16& a) {
   const int h = lane >> 5;
   f32x16 z = {0};
 #pragma unroll
-  for (int s = 0; s < D / 16; ++s) z = mfma32(row_frag<D>(st_lds, 0, s, lane), w.qf[s], z);
+  for (int s = 0; s < D / 16; ++s) z = mfma32(row_frag_at<D>(tile, lo, 0, s), w.qf[s], z);
   float mx = -INFINITY;
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
@@ -162,28 +200,27 @@ PASA_DEVICE void approx_chunk_zeroth(const char* st_lds, WaveState<D>& w, float 
   for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
     for (int t = 0; t < D / 32; ++t)
-      w.o[t] = mfma32(col_frag<D>(st_lds, 32 + 16 * ks, 32 * t, lane), pf[ks], w.o[t]);
+      w.o[t] = mfma32(col_frag_at<D>(tile, lo, 32 + 16 * ks, t), pf[ks], w.o[t]);
   a = z;
 }
 
-// First-order term of one group (Eq.14), 64 value columns at a time: O^T[part] += (scale Hg)^T (Q^T diag(A)),
+// First-order term of one group (Eq.14), 64 value columns at a time: O^T[part] += ((scale Hg)^T Q^T) diag(A),
 // A = sum of the chunk's a_j over the unselected blocks of the group.  h_lds holds rows
 // [64*part, 64*part + 64) of (scale Hg)^T as a K-like tile (row = value column, col = key column).
-template <int D>
-PASA_DEVICE void first_order_part(const char* h_lds, WaveState<D>& w, float A, int part, int lane) {
+template <int D, int PART>
+PASA_DEVICE void first_order_part(uint32_t tile, const LaneOffsets<D>& lo, WaveState<D>& w, float A) {
+  // q~ Hg for this lane's query (a lane owns one query, so its group weight A is a per-lane scalar
+  // that multiplies the finished product)
+  f32x16 w0 = {0}, w1 = {0};
 #pragma unroll
   for (int s = 0; s < D / 16; ++s) {
-    bf16x8 qs;
+    w0 = mfma32(row_frag_at<D>(tile, lo, 0, s), w.qf[s], w0);
+    w1 = mfma32(row_frag_at<D>(tile, lo, 32, s), w.qf[s], w1);
+  }
 #pragma unroll
-    for (int i = 0; i < 8; ++i) qs[i] = (__bf16)((float)w.qf[s][i] * A);
-    const bf16x8 a0 = row_frag<D>(h_lds, 0, s, lane), a1 = row_frag<D>(h_lds, 32, s, lane);
-    if (D == 64 || part == 0) {
-      w.o[0] = mfma32(a0, qs, w.o[0]);
-      w.o[1] = mfma32(a1, qs, w.o[1]);
-    } else {
-      w.o[D / 32 - 2] = mfma32(a0, qs, w.o[D / 32 - 2]);
-      w.o[D / 32 - 1] = mfma32(a1, qs, w.o[D / 32 - 1]);
-    }
+  for (int r = 0; r < 16; ++r) {
+    w.o[2 * PART][r] = fmaf(A, w0[r], w.o[2 * PART][r]);
+    w.o[2 * PART + 1][r] = fmaf(A, w1[r], w.o[2 * PART + 1][r]);
   }
 }
 
@@ -210,10 +247,13 @@ struct TileDma {
   PASA_DEVICE static int tile_row(int i, int wave, int lane) { return (i * kWaves + wave) * RPI + lane / CPR; }
   PASA_DEVICE static uint32_t chunk_off(int row, int lane) { return (uint32_t)(((lane % CPR) ^ swz<D>(row)) << 4); }
 
-  // all 64 rows are in bounds.  base, stride: wave-uniform.
-  PASA_DEVICE static void issue(const uint16_t* base, int64_t stride_elems, uint32_t lds, int wave, int lane) {
+  // per-lane byte offset of the lane's chunk in instruction 0 of its wave, for a given row stride
+  PASA_DEVICE static uint32_t lane_offset(int64_t stride_elems, int wave, int lane) {
     const int r = tile_row(0, wave, lane);
-    const uint32_t voff = (uint32_t)(r * stride_elems * 2) + chunk_off(r, lane);
+    return (uint32_t)(r * stride_elems * 2) + chunk_off(r, lane);
+  }
+  // all 64 rows are in bounds.  base, stride: wave-uniform; voff = lane_offset(stride).
+  PASA_DEVICE static void issue(const uint16_t* base, int64_t stride_elems, uint32_t voff, uint32_t lds, int wave) {
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
       const char* bi = reinterpret_cast<const char*>(base) + (int64_t)(i * kWaves * RPI) * stride_elems * 2;
@@ -269,7 +309,9 @@ struct UnionWalk {
   }
 };
 
-template <int D, bool SPARSE>
+// MULTI: the group has fewer than 32 blocks, so a chunk of 32 blocks intersects several groups and
+// the per-block weights of a chunk have to be kept until all of its group matrices have passed.
+template <int D, bool SPARSE, bool MULTI>
 __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
   constexpr int TILE_BYTES = 64 * 2 * D;
   constexpr int NI = TileDma<D>::NI;
@@ -286,10 +328,13 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
   int bh, qt, slice = 0;
   if (p.n_slices > 1) {  // (head, round, query tile) x XCD; XCD x walks slice x + 8 * round
     const int rounds = p.n_slices / kXcds;
-    qt = local % p.q_tiles;
     const int hr = local / p.q_tiles;
     slice = (hr % rounds) * kXcds + xcd;
     bh = hr / rounds;
+    // A query tile selects many more blocks from the slice it lies in than from the others, and
+    // workgroups are dispatched in id order: rotate the query-tile order per slice so that all XCDs
+    // are in their heavy (own-slice) stretch at the same time instead of one after the other.
+    qt = (int)((local % p.q_tiles + (int64_t)slice * p.q_tiles / p.n_slices) % p.q_tiles);
   } else {
     bh = local / p.q_tiles_per_xcd;
     qt = xcd * p.q_tiles_per_xcd + local % p.q_tiles_per_xcd;
@@ -309,7 +354,7 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
 #pragma unroll
   for (int s = 0; s < D / 16; ++s) {
     uint4 raw = {0u, 0u, 0u, 0u};
-    if (q_row < n) raw = *reinterpret_cast<const uint4*>(qb + (int64_t)q_row * p.stride_n + 16 * s + 8 * h);
+    if (q_row < n && !(kDebugModes && p.debug_mode == 4)) raw = *reinterpret_cast<const uint4*>(qb + (int64_t)q_row * p.stride_n + 16 * s + 8 * h);
     w.qf[s] = __builtin_bit_cast(bf16x8, raw);
   }
 #pragma unroll
@@ -368,99 +413,132 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
   auto first_group = [&](int chunk) { return (32 * chunk) / p.group; };
   auto last_group = [&](int chunk) { return (min(32 * chunk + 32, p.nb) - 1) / p.group; };
 
-  // ---- the producer side: a cursor over the tile stream, advanced once per ring slot ----
-  //   exact phase:   K tile, V tile of every step of the union walk (dense: of every 64 keys)
-  //   approx phase:  per chunk: statistics tile, then the HPARTS tiles of every group it intersects
+  // ---- the producer: a cursor over the tile stream.  produce() requests the next tile (if any) into
+  // ring slot `issued & 3` and returns its descriptor, which the consumer reads three tiles later:
+  //   bits 0-2 kind; bit 3 / bit 4: the block is in the first / second list;
+  //   K, V tiles:        bits 5-11  number of valid rows, clamped to [0, 64]
+  //   statistics, Hg:    bits 5-12  chunk, bit 13 part (which 64 value columns), bits 14-25 group
+  enum : uint32_t { kEnd = 0, kKTile = 1, kVTile = 2, kStats = 3, kHPart = 4 };
+  const uint32_t voff_kv = TileDma<D>::lane_offset(p.stride_n, wave, lane);
+  const uint32_t voff_ws = TileDma<D>::lane_offset(D, wave, lane);
   UnionWalk pw = make_walk();
-  int p_dense = 0;                            // dense: next tile
-  int p_side = 0;                             // 0: K next, 1: V next
-  const int c_end = approx_on ? c_hi : 0;     // chunks [c_lo, c_end) are approximated by this workgroup
+  int p_dense = 0;                               // dense: next tile
+  int p_side = 0;                                // 0: K next, 1: V next
+  const int c_end = approx_on ? c_hi : 0;        // chunks [c_lo, c_end) are approximated by this workgroup
   int p_chunk = c_lo, p_group = 0, p_part = -1;  // approx cursor; p_part == -1: statistics tile next
-  int issued = 0;                             // tiles requested so far
+  int issued = 0;                                // tiles requested so far
   bool p_exact_done = SPARSE ? pw.done() : false;  // a slice may hold no selected block at all
-  auto issue_next = [&]() {  // requests the next tile of the stream, if there is one
-    if (kDebugModes && p.debug_mode == 1 && issued >= kAhead) return;
-    const uint32_t dst = buf_addr(issued);
+  auto produce = [&]() -> uint32_t {
+    if (kDebugModes && p.debug_mode == 1 && issued >= kAhead) return kEnd;
+    const uint32_t dst = ring_base + (uint32_t)((issued & (kRing - 1)) * TILE_BYTES);
+    uint32_t desc;
     if (!p_exact_done) {
       const int r0 = SPARSE ? pw.block() * p.block + pw.sub * 64 : p_dense * 64;
       const uint16_t* src = p_side ? vb : kb;
       const int valid = n - r0;
-      if (valid >= 64) TileDma<D>::issue(src + (int64_t)r0 * p.stride_n, p.stride_n, dst, wave, lane);
+      if (valid >= 64) TileDma<D>::issue(src + (int64_t)r0 * p.stride_n, p.stride_n, voff_kv, dst, wave);
       else if (valid >= 1) TileDma<D>::issue_clamped(src + (int64_t)r0 * p.stride_n, p.stride_n, valid, dst, wave, lane);
       else TileDma<D>::issue_clamped(src + (int64_t)(n - 1) * p.stride_n, p.stride_n, 1, dst, wave, lane);
+      desc = (p_side ? kVTile : kKTile) | ((uint32_t)min(max(valid, 0), 64) << 5);
+      if constexpr (SPARSE) desc |= (pw.in_a() ? 8u : 0u) | (pw.in_b() ? 16u : 0u);
+      else desc |= 8u;
       if (p_side == 1) {
         if constexpr (SPARSE) { pw.advance(tiles_per_block); p_exact_done = pw.done(); }
         else { ++p_dense; p_exact_done = p_dense >= n_dense_tiles; }
       }
       p_side ^= 1;
-      ++issued;
     } else if (p_chunk < c_end) {
       if (p_part < 0) {
-        TileDma<D>::issue(st + (int64_t)p_chunk * 64 * D, D, dst, wave, lane);
+        TileDma<D>::issue(st + (int64_t)p_chunk * 64 * D, D, voff_ws, dst, wave);
+        desc = kStats | ((uint32_t)p_chunk << 5);
         p_group = first_group(p_chunk);
         p_part = 0;
       } else {
-        TileDma<D>::issue(hg + ((int64_t)p_group * D + 64 * p_part) * D, D, dst, wave, lane);
+        TileDma<D>::issue(hg + ((int64_t)p_group * D + 64 * p_part) * D, D, voff_ws, dst, wave);
+        desc = kHPart | ((uint32_t)p_chunk << 5) | ((uint32_t)p_part << 13) | ((uint32_t)p_group << 14);
         if (++p_part == HPARTS) {
           p_part = 0;
           if (++p_group > last_group(p_chunk)) { ++p_chunk; p_part = -1; }
         }
       }
-      ++issued;
+    } else {
+      return kEnd;
     }
+    ++issued;
+    return desc;
   };
 
-  // ---- the consumer side ----
-  int consumed = 0;  // tiles consumed so far == index of the tile being consumed
-  // Before reading tile `consumed`: wait for it, meet the other waves, refill the slot just freed.
-  auto acquire = [&]() {
-    ring_barrier<NI>(issued - consumed - 1);
-    issue_next();
+  // ---- the consumer: tile `it` of the stream lives in ring slot it & 3 ----
+  uint32_t d0 = kEnd, d1 = kEnd, d2 = kEnd;  // descriptors of the tiles requested but not yet consumed
+  int it = -kAhead;                          // index of the tile to consume next (negative: ring still filling)
+  // Moves on to the next tile: waits for it, meets the other waves (after which the slot of the
+  // previous tile is free) and requests one more tile.  Returns the descriptor of the tile to consume.
+  auto next_tile = [&]() -> uint32_t {
+    const uint32_t cur = d0;
+    if (cur != kEnd) ring_barrier<NI>((d1 != kEnd ? 1 : 0) + (d2 != kEnd ? 1 : 0));
+    d0 = d1;
+    d1 = d2;
+    d2 = (cur != kEnd || it < 0) ? produce() : kEnd;
+    return cur;
   };
-
+  auto slot = [&]() -> uint32_t { return ring_base + (uint32_t)((it & (kRing - 1)) * TILE_BYTES); };
+  LaneOffsets<D> lo;
+  lo.init(lane);
 #pragma unroll 1
-  for (int i = 0; i < kAhead; ++i) issue_next();
+  for (; it < 0; ++it) next_tile();  // fill the ring
 
-  // ---------------- exact tiles ----------------
-  {
-    UnionWalk cw = make_walk();
-    int c_dense = 0;
-    while (SPARSE ? !cw.done() : (c_dense < n_dense_tiles)) {
-      const int r0 = SPARSE ? cw.block() * p.block + cw.sub * 64 : c_dense * 64;
-      const bool mine = !SPARSE || (second ? cw.in_b() : cw.in_a());
-      bf16x8 pf[4];
-      acquire();
-      if (mine && !(kDebugModes && p.debug_mode == 2)) exact_tile_scores<D>(buf(consumed), w, p.c, n - r0, lane, pf);
-      ++consumed;
-      acquire();
-      if (mine && !(kDebugModes && p.debug_mode == 2)) exact_tile_pv<D>(buf(consumed), w, pf, lane);
-      ++consumed;
-      if constexpr (SPARSE) cw.advance(tiles_per_block);
-      else ++c_dense;
-    }
+  // ---------------- exact tiles: a K tile, then its V tile ----------------
+#pragma unroll 1
+  while ((d0 & 7u) == kKTile) {
+    bf16x8 pf[4];  // P^T of the tile
+    const uint32_t cur = next_tile();
+    const bool mine = qb_exists && ((cur >> (second ? 4 : 3)) & 1u) && !(kDebugModes && p.debug_mode == 2);
+    if (mine) exact_tile_scores<D>(slot(), lo, w, p.c, (int)((cur >> 5) & 127u), lane, pf);
+    ++it;
+    next_tile();
+    if (mine) exact_tile_pv<D>(slot(), lo, w, pf);
+    ++it;
   }
 
   // ---------------- grouped approximation of the unselected blocks ----------------
-  for (int chunk = c_lo; chunk < c_end; ++chunk) {
-    f32x16 a = {0};
-    acquire();
-    if (qb_exists)
-      approx_chunk_zeroth<D>(buf(consumed), w, p.c, mask_row[chunk], chunk, p.nb, p.block, p.tail, lane, a);
-    ++consumed;
-    const int g_last = last_group(chunk);
-    for (int g = first_group(chunk); g <= g_last; ++g) {
-      float A = 0.f;
+  // per chunk of 32 key blocks: its statistics tile, then for every group it intersects the HPARTS
+  // tiles of the group matrix
+#pragma unroll 1
+  while (d0 != kEnd) {
+    f32x16 a;  // a_j of the chunk
+    const uint32_t cur = next_tile();
+    const int chunk = (int)((cur >> 5) & 255u);
+    if (qb_exists) approx_chunk_zeroth<D>(slot(), lo, w, p.c, mask_row[chunk], chunk, p.nb, p.block, p.tail, lane, a);
+    ++it;
+    float A = 0.f;
+    if constexpr (!MULTI) {  // the whole chunk belongs to one group
+      if (qb_exists) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int j = 32 * chunk + mfma_row(r, h);
-        A += (j / p.group == g) ? a[r] : 0.f;
+        for (int r = 0; r < 16; ++r) A += a[r];
+        A = half_swap_sum(A);
       }
-      A = half_swap_sum(A);
+    }
+#pragma unroll 1
+    while ((d0 & 7u) == kHPart) {
+      if constexpr (MULTI) {
+        const int g = (int)((d0 >> 14) & 4095u);
+        A = 0.f;
+        if (qb_exists) {
 #pragma unroll
-      for (int part = 0; part < HPARTS; ++part) {
-        acquire();
-        if (qb_exists) first_order_part<D>(buf(consumed), w, A, part, lane);
-        ++consumed;
+          for (int r = 0; r < 16; ++r) {
+            const int j = 32 * chunk + mfma_row(r, h);
+            A += (j / p.group == g) ? a[r] : 0.f;
+          }
+          A = half_swap_sum(A);
+        }
+      }
+      next_tile();
+      if (qb_exists) first_order_part<D, 0>(slot(), lo, w, A);
+      ++it;
+      if constexpr (D == 128) {
+        next_tile();
+        if (qb_exists) first_order_part<D, 1>(slot(), lo, w, A);
+        ++it;
       }
     }
   }
@@ -468,6 +546,7 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
   // ---- epilogue ----
   const float l_tot = half_swap_sum(w.l);
   if (!(q_row < n && qb_exists)) return;
+  if (kDebugModes && p.debug_mode == 3) return;
   if (p.n_slices > 1) {  // leave the partial result of this slice to the merge kernel
     const int64_t prow = ((int64_t)bh * p.n_slices + slice) * n + q_row;
     float* orow = p.part_o + prow * D;
@@ -536,9 +615,9 @@ __global__ void __launch_bounds__(256) merge_kernel(AttnParams p) {
   if (p.lse && c4 == 0) p.lse[row] = (M + __builtin_amdgcn_logf(L)) * kLn2;
 }
 
-template <int D, bool SPARSE>
+template <int D, bool SPARSE, bool MULTI>
 hipError_t launch(const AttnParams& p, int grid, hipStream_t stream) {
-  hipLaunchKernelGGL((attn_kernel<D, SPARSE>), dim3(grid), dim3(kWaves * 64), 0, stream, p);
+  hipLaunchKernelGGL((attn_kernel<D, SPARSE, MULTI>), dim3(grid), dim3(kWaves * 64), 0, stream, p);
   return hipGetLastError();
 }
 
@@ -555,10 +634,11 @@ hipError_t pasa_launch_attn(AttnParams p, bool sparse, int d, hipStream_t stream
   if (!sparse) p.n_slices = 1;
   const int grid = p.n_slices > 1 ? p.bh * p.n_slices * p.q_tiles : p.bh * kXcds * p.q_tiles_per_xcd;
   hipError_t rc = hipErrorInvalidValue;
-  if (sparse && d == 128) rc = launch<128, true>(p, grid, stream);
-  else if (sparse && d == 64) rc = launch<64, true>(p, grid, stream);
-  else if (d == 128) rc = launch<128, false>(p, grid, stream);
-  else if (d == 64) rc = launch<64, false>(p, grid, stream);
+  const bool multi = sparse && p.group > 0 && p.group < 32;
+  if (sparse && d == 128) rc = multi ? launch<128, true, true>(p, grid, stream) : launch<128, true, false>(p, grid, stream);
+  else if (sparse && d == 64) rc = multi ? launch<64, true, true>(p, grid, stream) : launch<64, true, false>(p, grid, stream);
+  else if (d == 128) rc = launch<128, false, false>(p, grid, stream);
+  else if (d == 64) rc = launch<64, false, false>(p, grid, stream);
   if (rc != hipSuccess || p.n_slices == 1) return rc;
   const int64_t rows = (int64_t)p.bh * p.n;
   if (d == 128) {
