@@ -21,6 +21,7 @@ int check_shape(const pasa_shape_t* s) {
   if (!(s->scale >= 0.f) || isinf(s->scale)) return PASA_EINVAL;
   if (s->stride_n < s->d || s->stride_h < 1 || s->stride_b < 1) return PASA_EINVAL;
   if ((s->stride_n % 8) || (s->stride_h % 8) || (s->stride_b % 8)) return PASA_EALIGN;
+  if ((int64_t)s->n * s->stride_n * 2 >= ((int64_t)1 << 32)) return PASA_EUNSUPPORTED;  // 32-bit byte offsets inside a head
   return PASA_OK;
 }
 
@@ -37,7 +38,7 @@ int check_group(int group, int nb) {
 float effective_scale(const pasa_shape_t* s) { return s->scale > 0.f ? s->scale : 1.0f / sqrtf((float)s->d); }
 
 struct AttnWorkspace {
-  size_t st, hg, partial, part_o, part_ml, total;
+  size_t st, hg, partial, part_o, part_ml, queue, total;
   int n_groups, unit, n_units, n_chunks, n_slices;
 };
 
@@ -71,6 +72,7 @@ AttnWorkspace carve_attn(const pasa_shape_t* s) {
   if (w.n_slices > 1) {
     w.part_o = off; off = align_up(off + bh * w.n_slices * s->n * s->d * 4);
     w.part_ml = off; off = align_up(off + bh * w.n_slices * s->n * 2 * 4);
+    w.queue = off; off = align_up(off + 8 * 4);
   }
   if (s->group > 0) {
     const int group = s->group >= nb ? nb : s->group;
@@ -87,7 +89,12 @@ AttnWorkspace carve_attn(const pasa_shape_t* s) {
 
 }  // namespace
 
+static unsigned long long* g_prof = nullptr;  // experiments only
+
 extern "C" {
+
+// experiments only: device buffer of 32 uint64 receiving per-phase cycle sums (PASA_PROFILE_PHASES builds)
+__attribute__((visibility("default"))) void pasa_debug_set_prof(void* dev_buf) { g_prof = static_cast<unsigned long long*>(dev_buf); }
 
 const char* pasa_strerror(int status) {
   switch (status) {
@@ -230,6 +237,7 @@ static int attn_common(const void* q, const void* k, const void* v, const pasa_s
   a.stride_b = s.stride_b; a.stride_h = s.stride_h; a.stride_n = s.stride_n;
   a.bh = s.B * s.H; a.H = s.H; a.n = s.n; a.nb = nb; a.block = s.block; a.tail = s.n - (nb - 1) * s.block;
   a.scale = effective_scale(&s);
+  a.prof = g_prof;
   a.n_slices = 1;
   if (sparse) {
     a.idx = idx; a.mask = mask; a.k_sel = k_sel; a.mask_words = (nb + 31) / 32;
@@ -241,6 +249,7 @@ static int attn_common(const void* q, const void* k, const void* v, const pasa_s
     a.n_slices = w.n_slices;
     a.part_o = reinterpret_cast<float*>(base + w.part_o);
     a.part_ml = reinterpret_cast<float*>(base + w.part_ml);
+    a.queue = reinterpret_cast<uint32_t*>(base + w.queue);
   }
   return pasa_launch_attn(a, sparse, s.d, static_cast<hipStream_t>(stream)) == hipSuccess ? PASA_OK : PASA_EHIP;
 }

@@ -46,6 +46,12 @@ constexpr bool kDebugModes = true;   // timing experiments: results are wrong on
 #else
 constexpr bool kDebugModes = false;
 #endif
+#ifdef PASA_PROFILE_PHASES
+constexpr bool kProfile = true;      // per-phase cycle counts of the exact loop into AttnParams::prof
+#else
+constexpr bool kProfile = false;
+#endif
+PASA_DEVICE uint32_t clock32() { return (uint32_t)__builtin_amdgcn_s_memtime(); }
 
 typedef __attribute__((address_space(4))) const int32_t const_i32;
 typedef __attribute__((address_space(4))) const uint32_t const_u32;
@@ -94,6 +100,12 @@ PASA_DEVICE bf16x8 col_frag_at(uint32_t tile, const LaneOffsets<D>& lo, int row0
   return __builtin_bit_cast(bf16x8, v);
 }
 
+PASA_DEVICE float max3(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
 // Raise the running maximum of a lane to m_new and rescale its accumulators.  Called only when some
 // lane of the wave needs it (the branch around it is wave-uniform).
 template <int D>
@@ -129,7 +141,7 @@ PASA_DEVICE void exact_tile_scores(uint32_t tile, const LaneOffsets<D>& lo, Wave
   }
   float mx = fmaxf(s0[0], s1[0]);
 #pragma unroll
-  for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(s0[r], s1[r]));
+  for (int r = 1; r < 16; ++r) mx = max3(mx, s0[r], s1[r]);
   mx = half_swap_max(mx) * c;
   if (__builtin_amdgcn_ballot_w64(mx > w.m)) rescale<D>(w, fmaxf(w.m, mx));
   const float neg = -w.m;
@@ -247,18 +259,20 @@ struct TileDma {
   PASA_DEVICE static int tile_row(int i, int wave, int lane) { return (i * kWaves + wave) * RPI + lane / CPR; }
   PASA_DEVICE static uint32_t chunk_off(int row, int lane) { return (uint32_t)(((lane % CPR) ^ swz<D>(row)) << 4); }
 
-  // per-lane byte offset of the lane's chunk in instruction 0 of its wave, for a given row stride
-  PASA_DEVICE static uint32_t lane_offset(int64_t stride_elems, int wave, int lane) {
-    const int r = tile_row(0, wave, lane);
-    return (uint32_t)(r * stride_elems * 2) + chunk_off(r, lane);
-  }
-  // all 64 rows are in bounds.  base, stride: wave-uniform; voff = lane_offset(stride).
-  PASA_DEVICE static void issue(const uint16_t* base, int64_t stride_elems, uint32_t voff, uint32_t lds, int wave) {
+  // per-lane byte offsets of the lane's chunk in each of the wave's NI instructions, for a given row
+  // stride (a lane's swizzle is the same in all of them; the rows are kWaves*RPI apart)
+  PASA_DEVICE static void lane_offsets(int64_t stride_elems, int wave, int lane, uint32_t (&voff)[NI]) {
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
-      const char* bi = reinterpret_cast<const char*>(base) + (int64_t)(i * kWaves * RPI) * stride_elems * 2;
-      dma_1k(bi, voff, lds + (uint32_t)((i * kWaves + wave) * 1024));
+      const int r = tile_row(i, wave, lane);
+      voff[i] = (uint32_t)(r * stride_elems * 2) + chunk_off(r, lane);
     }
+  }
+  // all 64 rows are in bounds.  base: wave-uniform address of the tile's first row; lds_wave: LDS
+  // address of the slot plus wave*1024.
+  PASA_DEVICE static void issue(const void* base, const uint32_t (&voff)[NI], uint32_t lds_wave) {
+#pragma unroll
+    for (int i = 0; i < NI; ++i) dma_1k(base, voff[i], lds_wave + (uint32_t)(i * kWaves * 1024));
   }
   // tile rows at or beyond `valid` (>= 1) re-read row valid-1 of the tile (finite stand-ins for rows
   // that do not exist; the caller masks them out).
@@ -318,24 +332,53 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
   constexpr int HPARTS = D / 64;  // 64-row tiles per group matrix
   __shared__ __attribute__((aligned(1024))) char ring[kRing * TILE_BYTES];
 
+  __shared__ int s_item;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int ql = lane & 31, h = lane >> 5;
-  // Workgroup -> (head, query tile[, key slice]).  The hardware deals consecutive workgroup ids
-  // round-robin to the 8 XCDs.  Without slicing, ids are decoded such that one XCD owns a contiguous
-  // run of query tiles of one head and all XCDs work on the same head at the same time.
-  const int xcd = blockIdx.x % kXcds, local = blockIdx.x / kXcds;
+  const uint32_t ring_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)ring;
+  LaneOffsets<D> lo;
+  lo.init(lane);
+  uint32_t voff_kv[NI], voff_ws[NI];  // lane offsets of the tile loads: rows of K/V (caller's stride), workspace tiles
+  TileDma<D>::lane_offsets(p.stride_n, wave, lane, voff_kv);
+  TileDma<D>::lane_offsets(D, wave, lane, voff_ws);
+  const uint32_t ring_wave = ring_base + (uint32_t)(wave * 1024);
+  const uint32_t row_bytes = (uint32_t)(p.stride_n * 2);
+  int issued = 0;  // tiles requested so far; tile i goes to ring slot i & 3 (keeps counting across work items)
+  int it = 0;      // tiles consumed so far
+  const bool persistent = p.n_slices > 1;
+  int xcd = blockIdx.x % kXcds;
+  if (persistent) {  // ask the hardware which XCD this workgroup really runs on
+    unsigned id;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(id));
+    xcd = (int)(id & 15u) % kXcds;
+  }
+
+  // Work items.  Without key-range slicing a workgroup handles exactly one (head, query tile): the
+  // hardware deals consecutive workgroup ids round-robin to the 8 XCDs, and ids are decoded such
+  // that one XCD owns a contiguous run of query tiles of one head and all XCDs work on the same head
+  // at the same time.  With slicing the kernel is persistent: two workgroups per CU, each taking
+  // (head, round, query tile) items from the queue of the XCD it runs on until the queue is empty;
+  // XCD x walks key slice x + 8 * round.  (A plain grid would not do: workgroups are dispatched in
+  // id order, ids are bound to XCDs, and the items of one XCD take very different times -- a
+  // query tile selects many more blocks from the slice it lies in -- so one busy XCD would hold up
+  // the dispatch to all the others.)
+  for (;;) {
   int bh, qt, slice = 0;
-  if (p.n_slices > 1) {  // (head, round, query tile) x XCD; XCD x walks slice x + 8 * round
+  if (persistent) {
+    if (tid == 0) s_item = (int)atomicAdd(p.queue + xcd, 1u);
+    __syncthreads();
+    const int item = s_item;
+    __syncthreads();  // everyone has read s_item before it can be written again
+    if (item >= p.items_per_xcd) return;  // queue empty: every wave of the workgroup leaves here
     const int rounds = p.n_slices / kXcds;
-    const int hr = local / p.q_tiles;
+    const int hr = item / p.q_tiles;
     slice = (hr % rounds) * kXcds + xcd;
     bh = hr / rounds;
-    // A query tile selects many more blocks from the slice it lies in than from the others, and
-    // workgroups are dispatched in id order: rotate the query-tile order per slice so that all XCDs
-    // are in their heavy (own-slice) stretch at the same time instead of one after the other.
-    qt = (int)((local % p.q_tiles + (int64_t)slice * p.q_tiles / p.n_slices) % p.q_tiles);
+    // start each slice's sweep over the query tiles at the tiles that lie in the slice itself
+    qt = (int)((item % p.q_tiles + (int64_t)slice * p.q_tiles / p.n_slices) % p.q_tiles);
   } else {
+    const int local = blockIdx.x / kXcds;
     bh = local / p.q_tiles_per_xcd;
     qt = xcd * p.q_tiles_per_xcd + local % p.q_tiles_per_xcd;
     if (qt >= p.q_tiles) return;  // padding workgroup (the whole workgroup leaves before any barrier)
@@ -346,9 +389,6 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
   const uint16_t* const vb = p.v + head_off;
   const int n = p.n;
   const int q_row = qt * 128 + wave * 32 + ql;
-  const uint32_t ring_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)ring;
-  auto buf = [&](int item) -> const char* { return ring + (item & (kRing - 1)) * TILE_BYTES; };
-  auto buf_addr = [&](int item) -> uint32_t { return ring_base + (uint32_t)((item & (kRing - 1)) * TILE_BYTES); };
 
   WaveState<D> w;
 #pragma unroll
@@ -413,92 +453,113 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
   auto first_group = [&](int chunk) { return (32 * chunk) / p.group; };
   auto last_group = [&](int chunk) { return (min(32 * chunk + 32, p.nb) - 1) / p.group; };
 
-  // ---- the producer: a cursor over the tile stream.  produce() requests the next tile (if any) into
-  // ring slot `issued & 3` and returns its descriptor, which the consumer reads three tiles later:
+  // ---- the producers.  A tile that is requested goes to ring slot `issued & 3`; the consumer learns what it
+  // is from a descriptor:
   //   bits 0-2 kind; bit 3 / bit 4: the block is in the first / second list;
-  //   K, V tiles:        bits 5-11  number of valid rows, clamped to [0, 64]
-  //   statistics, Hg:    bits 5-12  chunk, bit 13 part (which 64 value columns), bits 14-25 group
-  enum : uint32_t { kEnd = 0, kKTile = 1, kVTile = 2, kStats = 3, kHPart = 4 };
-  const uint32_t voff_kv = TileDma<D>::lane_offset(p.stride_n, wave, lane);
-  const uint32_t voff_ws = TileDma<D>::lane_offset(D, wave, lane);
+  //   K tiles:           bits 5-11  number of valid rows, clamped to [0, 64]  (its V tile follows it)
+  //   statistics, Hg:    bits 5-12  chunk, bits 14-25 group
+  enum : uint32_t { kEnd = 0, kKTile = 1, kStats = 3, kHPart = 4 };
+  auto slot = [&](int i) -> uint32_t { return ring_base + (uint32_t)((i & (kRing - 1)) * TILE_BYTES); };
+  auto slot_wave = [&](int i) -> uint32_t { return ring_wave + (uint32_t)((i & (kRing - 1)) * TILE_BYTES); };
+
+  // exact phase: requests the K tile and the V tile of the next step of the walk into the next two slots
   UnionWalk pw = make_walk();
-  int p_dense = 0;                               // dense: next tile
-  int p_side = 0;                                // 0: K next, 1: V next
+  int p_dense = 0;  // dense: next tile
+  auto produce_pair = [&]() -> uint32_t {
+    if (SPARSE ? pw.done() : (p_dense >= n_dense_tiles)) return kEnd;
+    if (kDebugModes && p.debug_mode == 1 && issued >= 2) { issued += 2; if constexpr (SPARSE) pw.advance(tiles_per_block); else ++p_dense; return kKTile | 8u | 16u | (64u << 5); }
+    const int r0 = SPARSE ? pw.block() * p.block + pw.sub * 64 : p_dense * 64;
+    const int valid = n - r0;
+    uint32_t desc = kKTile | ((uint32_t)min(max(valid, 0), 64) << 5);
+    if constexpr (SPARSE) desc |= (pw.in_a() ? 8u : 0u) | (pw.in_b() ? 16u : 0u);
+    else desc |= 8u;
+    if (valid >= 64) {
+      const uint32_t off = (uint32_t)r0 * row_bytes;
+      TileDma<D>::issue(reinterpret_cast<const char*>(kb) + off, voff_kv, slot_wave(issued));
+      TileDma<D>::issue(reinterpret_cast<const char*>(vb) + off, voff_kv, slot_wave(issued + 1));
+    } else {  // the ragged last tile, or the tile after it in a 128-token block: rows past the end re-read the last row
+      const int rr = valid >= 1 ? r0 : n - 1, vv = valid >= 1 ? valid : 1;
+      TileDma<D>::issue_clamped(kb + (int64_t)rr * p.stride_n, p.stride_n, vv, slot(issued), wave, lane);
+      TileDma<D>::issue_clamped(vb + (int64_t)rr * p.stride_n, p.stride_n, vv, slot(issued + 1), wave, lane);
+    }
+    issued += 2;
+    if constexpr (SPARSE) pw.advance(tiles_per_block);
+    else ++p_dense;
+    return desc;
+  };
+
+  // approximation phase: requests the next tile: per chunk its statistics tile, then the HPARTS tiles of
+  // every group matrix the chunk intersects
   const int c_end = approx_on ? c_hi : 0;        // chunks [c_lo, c_end) are approximated by this workgroup
-  int p_chunk = c_lo, p_group = 0, p_part = -1;  // approx cursor; p_part == -1: statistics tile next
-  int issued = 0;                                // tiles requested so far
-  bool p_exact_done = SPARSE ? pw.done() : false;  // a slice may hold no selected block at all
-  auto produce = [&]() -> uint32_t {
-    if (kDebugModes && p.debug_mode == 1 && issued >= kAhead) return kEnd;
-    const uint32_t dst = ring_base + (uint32_t)((issued & (kRing - 1)) * TILE_BYTES);
+  int p_chunk = c_lo, p_group = 0, p_part = -1;  // p_part == -1: statistics tile next
+  auto produce_approx = [&]() -> uint32_t {
+    if (p_chunk >= c_end) return kEnd;
     uint32_t desc;
-    if (!p_exact_done) {
-      const int r0 = SPARSE ? pw.block() * p.block + pw.sub * 64 : p_dense * 64;
-      const uint16_t* src = p_side ? vb : kb;
-      const int valid = n - r0;
-      if (valid >= 64) TileDma<D>::issue(src + (int64_t)r0 * p.stride_n, p.stride_n, voff_kv, dst, wave);
-      else if (valid >= 1) TileDma<D>::issue_clamped(src + (int64_t)r0 * p.stride_n, p.stride_n, valid, dst, wave, lane);
-      else TileDma<D>::issue_clamped(src + (int64_t)(n - 1) * p.stride_n, p.stride_n, 1, dst, wave, lane);
-      desc = (p_side ? kVTile : kKTile) | ((uint32_t)min(max(valid, 0), 64) << 5);
-      if constexpr (SPARSE) desc |= (pw.in_a() ? 8u : 0u) | (pw.in_b() ? 16u : 0u);
-      else desc |= 8u;
-      if (p_side == 1) {
-        if constexpr (SPARSE) { pw.advance(tiles_per_block); p_exact_done = pw.done(); }
-        else { ++p_dense; p_exact_done = p_dense >= n_dense_tiles; }
-      }
-      p_side ^= 1;
-    } else if (p_chunk < c_end) {
-      if (p_part < 0) {
-        TileDma<D>::issue(st + (int64_t)p_chunk * 64 * D, D, voff_ws, dst, wave);
-        desc = kStats | ((uint32_t)p_chunk << 5);
-        p_group = first_group(p_chunk);
-        p_part = 0;
-      } else {
-        TileDma<D>::issue(hg + ((int64_t)p_group * D + 64 * p_part) * D, D, voff_ws, dst, wave);
-        desc = kHPart | ((uint32_t)p_chunk << 5) | ((uint32_t)p_part << 13) | ((uint32_t)p_group << 14);
-        if (++p_part == HPARTS) {
-          p_part = 0;
-          if (++p_group > last_group(p_chunk)) { ++p_chunk; p_part = -1; }
-        }
-      }
+    if (p_part < 0) {
+      TileDma<D>::issue(st + (int64_t)p_chunk * 64 * D, voff_ws, slot_wave(issued));
+      desc = kStats | ((uint32_t)p_chunk << 5);
+      p_group = first_group(p_chunk);
+      p_part = 0;
     } else {
-      return kEnd;
+      TileDma<D>::issue(hg + ((int64_t)p_group * D + 64 * p_part) * D, voff_ws, slot_wave(issued));
+      desc = kHPart | ((uint32_t)p_chunk << 5) | ((uint32_t)p_group << 14);
+      if (++p_part == HPARTS) {
+        p_part = 0;
+        if (++p_group > last_group(p_chunk)) { ++p_chunk; p_part = -1; }
+      }
     }
     ++issued;
     return desc;
   };
 
   // ---- the consumer: tile `it` of the stream lives in ring slot it & 3 ----
-  uint32_t d0 = kEnd, d1 = kEnd, d2 = kEnd;  // descriptors of the tiles requested but not yet consumed
-  int it = -kAhead;                          // index of the tile to consume next (negative: ring still filling)
-  // Moves on to the next tile: waits for it, meets the other waves (after which the slot of the
-  // previous tile is free) and requests one more tile.  Returns the descriptor of the tile to consume.
+  uint32_t d0 = kEnd, d1 = kEnd, d2 = kEnd;  // approximation tiles requested but not yet consumed, in order
+
+  // ---------------- exact tiles: one barrier per (K tile, V tile) pair ----------------
+  // While a pair is being consumed the next pair (or the head of the approximation stream) is on its
+  // way into the other two ring slots.
+  uint32_t prof[6] = {0, 0, 0, 0, 0, 0};  // cycles: wait, scores, produce, PV; steps mine, steps not mine
+  uint32_t dk = produce_pair();
+  if (dk == kEnd) { d0 = produce_approx(); d1 = produce_approx(); }
+#pragma unroll 1
+  while (dk != kEnd) {
+    bf16x8 pf[4];  // P^T of the tile
+    const uint32_t t0 = kProfile ? clock32() : 0u;
+    ring_barrier<NI>(0);  // the pair has landed; every wave is done with the previous pair
+    const uint32_t tb = kProfile ? clock32() : 0u;
+    const uint32_t cur = dk;
+    dk = produce_pair();
+    if (dk == kEnd) { d0 = produce_approx(); d1 = produce_approx(); }
+    const bool mine = qb_exists && ((cur >> (second ? 4 : 3)) & 1u) && !(kDebugModes && p.debug_mode == 2);
+    const uint32_t t1 = kProfile ? clock32() : 0u;
+    if (mine) exact_tile_scores<D>(slot(it), lo, w, p.c, (int)((cur >> 5) & 127u), lane, pf);
+    const uint32_t t2 = kProfile ? clock32() : 0u;
+    if (mine) exact_tile_pv<D>(slot(it + 1), lo, w, pf);
+    it += 2;
+    if (kProfile) {
+      const uint32_t t4 = clock32();
+      prof[0] += tb - t0; prof[2] += t1 - tb; prof[1] += t2 - t1; prof[3] += t4 - t2;
+      prof[mine ? 4 : 5] += 1;
+    }
+  }
+  if (kProfile && p.prof && lane == 0) {
+    for (int x = 0; x < 6; ++x) atomicAdd(p.prof + wave * 8 + x, (unsigned long long)prof[x]);
+  }
+
+  // Moves on to the next tile of the approximation stream: waits for it, meets the other waves (after
+  // which the slots of all earlier tiles are free) and tops the ring up to three tiles ahead.
+  // Returns the descriptor of the tile to consume (slot(it)).
   auto next_tile = [&]() -> uint32_t {
     const uint32_t cur = d0;
-    if (cur != kEnd) ring_barrier<NI>((d1 != kEnd ? 1 : 0) + (d2 != kEnd ? 1 : 0));
+    ring_barrier<NI>((d1 != kEnd ? 1 : 0) + (d2 != kEnd ? 1 : 0));
     d0 = d1;
     d1 = d2;
-    d2 = (cur != kEnd || it < 0) ? produce() : kEnd;
+    d2 = kEnd;
+    if (d0 == kEnd) d0 = produce_approx();
+    if (d1 == kEnd && d0 != kEnd) d1 = produce_approx();
+    if (d2 == kEnd && d1 != kEnd) d2 = produce_approx();
     return cur;
   };
-  auto slot = [&]() -> uint32_t { return ring_base + (uint32_t)((it & (kRing - 1)) * TILE_BYTES); };
-  LaneOffsets<D> lo;
-  lo.init(lane);
-#pragma unroll 1
-  for (; it < 0; ++it) next_tile();  // fill the ring
-
-  // ---------------- exact tiles: a K tile, then its V tile ----------------
-#pragma unroll 1
-  while ((d0 & 7u) == kKTile) {
-    bf16x8 pf[4];  // P^T of the tile
-    const uint32_t cur = next_tile();
-    const bool mine = qb_exists && ((cur >> (second ? 4 : 3)) & 1u) && !(kDebugModes && p.debug_mode == 2);
-    if (mine) exact_tile_scores<D>(slot(), lo, w, p.c, (int)((cur >> 5) & 127u), lane, pf);
-    ++it;
-    next_tile();
-    if (mine) exact_tile_pv<D>(slot(), lo, w, pf);
-    ++it;
-  }
 
   // ---------------- grouped approximation of the unselected blocks ----------------
   // per chunk of 32 key blocks: its statistics tile, then for every group it intersects the HPARTS
@@ -508,7 +569,7 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
     f32x16 a;  // a_j of the chunk
     const uint32_t cur = next_tile();
     const int chunk = (int)((cur >> 5) & 255u);
-    if (qb_exists) approx_chunk_zeroth<D>(slot(), lo, w, p.c, mask_row[chunk], chunk, p.nb, p.block, p.tail, lane, a);
+    if (qb_exists) approx_chunk_zeroth<D>(slot(it), lo, w, p.c, mask_row[chunk], chunk, p.nb, p.block, p.tail, lane, a);
     ++it;
     float A = 0.f;
     if constexpr (!MULTI) {  // the whole chunk belongs to one group
@@ -533,11 +594,11 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
         }
       }
       next_tile();
-      if (qb_exists) first_order_part<D, 0>(slot(), lo, w, A);
+      if (qb_exists) first_order_part<D, 0>(slot(it), lo, w, A);
       ++it;
       if constexpr (D == 128) {
         next_tile();
-        if (qb_exists) first_order_part<D, 1>(slot(), lo, w, A);
+        if (qb_exists) first_order_part<D, 1>(slot(it), lo, w, A);
         ++it;
       }
     }
@@ -545,41 +606,47 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
 
   // ---- epilogue ----
   const float l_tot = half_swap_sum(w.l);
-  if (!(q_row < n && qb_exists)) return;
-  if (kDebugModes && p.debug_mode == 3) return;
-  if (p.n_slices > 1) {  // leave the partial result of this slice to the merge kernel
-    const int64_t prow = ((int64_t)bh * p.n_slices + slice) * n + q_row;
-    float* orow = p.part_o + prow * D;
+  if (q_row < n && qb_exists && !(kDebugModes && p.debug_mode == 3)) {
+    if (p.n_slices > 1) {  // leave the partial result of this slice to the merge kernel
+      const int64_t prow = ((int64_t)bh * p.n_slices + slice) * n + q_row;
+      float* orow = p.part_o + prow * D;
 #pragma unroll
-    for (int t = 0; t < D / 32; ++t)
+      for (int t = 0; t < D / 32; ++t)
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        typedef float f32x4 __attribute__((ext_vector_type(4)));
-        f32x4 ov;
+        for (int g = 0; g < 4; ++g) {
+          typedef float f32x4 __attribute__((ext_vector_type(4)));
+          f32x4 ov;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) ov[r] = w.o[t][4 * g + r];
-        __builtin_nontemporal_store(ov, reinterpret_cast<f32x4*>(orow + 32 * t + 8 * g + 4 * h));
+          for (int r = 0; r < 4; ++r) ov[r] = w.o[t][4 * g + r];
+          __builtin_nontemporal_store(ov, reinterpret_cast<f32x4*>(orow + 32 * t + 8 * g + 4 * h));
+        }
+      if (h == 0) {
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
+        f32x2 ml = {w.m, l_tot};
+        __builtin_nontemporal_store(ml, reinterpret_cast<f32x2*>(p.part_ml + prow * 2));
       }
-    if (h == 0) {
-      typedef float f32x2 __attribute__((ext_vector_type(2)));
-      f32x2 ml = {w.m, l_tot};
-      __builtin_nontemporal_store(ml, reinterpret_cast<f32x2*>(p.part_ml + prow * 2));
+    } else {
+      const float inv = 1.0f / l_tot;
+      uint16_t* orow = p.o + head_off + (int64_t)q_row * p.stride_n;
+#pragma unroll
+      for (int t = 0; t < D / 32; ++t)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+          bf16x4 ov;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) ov[r] = (__bf16)(w.o[t][4 * g + r] * inv);
+          *reinterpret_cast<bf16x4*>(orow + 32 * t + 8 * g + 4 * h) = ov;
+        }
+      if (p.lse && h == 0) p.lse[(int64_t)bh * n + q_row] = (w.m + __builtin_amdgcn_logf(l_tot)) * kLn2;
     }
-    return;
   }
-  const float inv = 1.0f / l_tot;
-  uint16_t* orow = p.o + head_off + (int64_t)q_row * p.stride_n;
-#pragma unroll
-  for (int t = 0; t < D / 32; ++t)
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-      bf16x4 ov;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) ov[r] = (__bf16)(w.o[t][4 * g + r] * inv);
-      *reinterpret_cast<bf16x4*>(orow + 32 * t + 8 * g + 4 * h) = ov;
-    }
-  if (p.lse && h == 0) p.lse[(int64_t)bh * n + q_row] = (w.m + __builtin_amdgcn_logf(l_tot)) * kLn2;
+  if (!persistent) return;
+  }  // next work item
+}
+
+__global__ void reset_queue_kernel(uint32_t* queue) {
+  if (threadIdx.x < kXcds) queue[threadIdx.x] = 0u;
 }
 
 // Merge of the per-slice partial results of a row:  M = max_s m_s,  w_s = 2^(m_s - M),
@@ -632,7 +699,12 @@ hipError_t pasa_launch_attn(AttnParams p, bool sparse, int d, hipStream_t stream
   p.q_tiles = (p.n + 127) / 128;  // 128 query rows per workgroup
   p.q_tiles_per_xcd = (p.q_tiles + kXcds - 1) / kXcds;
   if (!sparse) p.n_slices = 1;
-  const int grid = p.n_slices > 1 ? p.bh * p.n_slices * p.q_tiles : p.bh * kXcds * p.q_tiles_per_xcd;
+  int grid = p.bh * kXcds * p.q_tiles_per_xcd;
+  if (p.n_slices > 1) {  // persistent: two workgroups per CU (64 KB of LDS each), work queues per XCD
+    p.items_per_xcd = p.bh * (p.n_slices / kXcds) * p.q_tiles;
+    grid = 2 * 256;
+    hipLaunchKernelGGL(reset_queue_kernel, dim3(1), dim3(64), 0, stream, p.queue);
+  }
   hipError_t rc = hipErrorInvalidValue;
   const bool multi = sparse && p.group > 0 && p.group < 32;
   if (sparse && d == 128) rc = multi ? launch<128, true, true>(p, grid, stream) : launch<128, true, false>(p, grid, stream);

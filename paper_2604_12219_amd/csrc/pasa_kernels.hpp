@@ -14,6 +14,7 @@ struct AttnParams {
   int64_t stride_b, stride_h, stride_n;
   int32_t bh, H, n, nb, block, tail;  // tail = valid tokens of the last block
   float scale, c;                     // c = scale * log2(e), filled in by the launcher
+  unsigned long long* prof;           // experiments only (PASA_PROFILE_PHASES builds): [4 waves][8] cycle sums
   int32_t debug_mode;                 // experiments only (PASA_DEBUG_MODES builds): 1 = no tile loads, 2 = no math
   int32_t q_tiles, q_tiles_per_xcd;   // filled in by the launcher
   // sparse path only
@@ -28,6 +29,8 @@ struct AttnParams {
   int32_t n_slices;      // 1 = off (the attention kernel writes the output itself)
   float* part_o;         // fp32 [BH][n_slices][n][d]: unnormalised partial numerators
   float* part_ml;        // fp32 [BH][n_slices][n][2]: running maximum (log2 units) and partial normaliser
+  uint32_t* queue;       // [8] work-item counters, one per XCD (reset by the launcher)
+  int32_t items_per_xcd; // filled in by the launcher
 };
 
 // dense (sparse = false) or piecewise sparse attention; d in {64,128}, block in {64,128}
