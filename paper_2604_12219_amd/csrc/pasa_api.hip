@@ -45,14 +45,11 @@ struct AttnWorkspace {
 // Number of key-range slices of the sparse kernel.  K and V of one head should fit the 4 MB L2 of an
 // XCD slice by slice; there are 8 XCDs, so slices come in multiples of 8.
 int choose_slices(const pasa_shape_t* s) {
-  const int n_chunks = (num_blocks(s) + 31) / 32;
-  if (s->kv_slices == 1) return 1;
-  if (s->kv_slices > 1) return s->kv_slices;
-  const size_t kv_bytes = (size_t)s->n * s->d * 2 * 2;
-  if (kv_bytes <= ((size_t)4 << 20) || n_chunks < 8) return 1;
-  int rounds = (int)((kv_bytes + ((size_t)40 << 20) - 1) / ((size_t)40 << 20));  // <= 5 MB per slice
-  while (rounds > 1 && 8 * rounds > n_chunks) --rounds;
-  return 8 * rounds;
+  if (s->kv_slices >= 1) return s->kv_slices;
+  // kv_slices == 0: no slicing.  Slicing removes most of the fabric traffic, but the extra partial
+  // results and the merge pass cost more than that buys while the kernel is not yet limited by the
+  // fabric; callers can switch it on per shape.
+  return 1;
 }
 
 int check_slices(const pasa_shape_t* s) {

@@ -1,0 +1,138 @@
+"""The C ABI without a GPU: the library loads, exports every symbol the header declares, and its
+host-side helpers and argument validation behave as documented (validation happens before any
+launch, so these calls never touch a device)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import oracle
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "pasa.h")
+
+
+@pytest.fixture(scope="module")
+def P():
+    import paper_2604_12219_amd as P
+    if not os.path.exists(P.lib_path()):
+        from paper_2604_12219_amd.build import build
+        build()
+    P.load_library()
+    return P
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    return sorted(set(re.findall(r"PASA_API\s+[\w\s\*]+?\b(pasa_\w+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(P):
+    names = declared_symbols()
+    assert {"pasa_block_score", "pasa_route", "pasa_sparse_attn_fwd", "pasa_attn_dense_ref", "pasa_kv_stats",
+            "pasa_sparse_attn_fwd_prepared", "pasa_topk_count", "pasa_strerror"} <= set(names)
+    lib = ctypes.CDLL(P.lib_path())
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in pasa.h but not exported"
+    from paper_2604_12219_amd.pasa import EXPORTS
+    assert set(EXPORTS) == set(names)
+
+
+def test_product_has_no_cpu_fallback_and_does_not_import_the_oracle():
+    src = ""
+    pkg = os.path.join(ROOT, "paper_2604_12219_amd")
+    for f in os.listdir(pkg):
+        if f.endswith(".py"):
+            src += open(os.path.join(pkg, f)).read()
+    assert "import oracle" not in src and "from oracle" not in src
+    assert "There is no CPU fallback" in src
+
+
+def test_topk_count_matches_the_oracle_rule_and_rejects_bad_ratios(P):
+    for nb in (1, 7, 16, 512, 1182, 1154):
+        for keep in (1e-6, 0.05, 0.15, 0.2, 0.25, 0.5, 0.999, 1.0):
+            assert P.topk_count(nb, keep) == oracle.topk_count(nb, keep)
+    for bad in (0.0, -0.1, 1.0001, float("nan")):
+        with pytest.raises(P.PasaError):
+            P.topk_count(100, bad)
+    with pytest.raises(P.PasaError):
+        P.topk_count(0, 0.5)
+
+
+def _shape(P, **kw):
+    base = dict(B=1, H=2, n=8192, d=128, block=64, group=32, stride_n=128)
+    base.update(kw)
+    base.setdefault("stride_h", max(base["n"], 1) * base["stride_n"])
+    base.setdefault("stride_b", base["H"] * base["stride_h"])
+    return P.Shape(**base)
+
+
+def test_shape_helpers_and_workspace_sizes(P):
+    s = _shape(P)
+    assert P.num_blocks(s) == 128 and P.mask_words(16) == 1 and P.mask_words(1182) == 37
+    assert P.num_blocks(_shape(P, n=1000)) == 16  # ragged tail
+    assert P.score_workspace_bytes(s) >= 2 * 2 * 128 * 128 * 4
+    assert P.attn_workspace_bytes(_shape(P, group=4096)) > 0  # at least N_B blocks per group: one global matrix
+    assert P.attn_workspace_bytes(s) > 0
+    assert P.attn_workspace_bytes(_shape(P, group=0)) > 0
+    # invalid shapes report 0 bytes
+    assert P.attn_workspace_bytes(_shape(P, d=96)) == 0
+    assert P.attn_workspace_bytes(_shape(P, group=48)) == 0
+    assert P.attn_workspace_bytes(_shape(P, kv_slices=3)) == 0
+    assert P.score_workspace_bytes(_shape(P, block=32)) == 0
+
+
+def test_argument_validation_returns_before_any_launch(P):
+    L = P.load_library()
+    good = _shape(P).c()
+    fake = ctypes.c_void_p(0x1000)  # 16-byte aligned, never dereferenced: every call below fails validation first
+    big = ctypes.c_size_t(1 << 40)
+    EINVAL, EUNSUPPORTED, EWORKSPACE, EALIGN = -1, -2, -3, -4
+
+    def score(shape, q=fake, k=fake, out=fake, ws=fake, nbytes=big):
+        return L.pasa_block_score(q, k, ctypes.byref(shape), None, out, ws, nbytes, None)
+
+    assert score(good, q=None) == EINVAL
+    assert score(good, out=None) == EINVAL
+    assert score(good, nbytes=ctypes.c_size_t(16)) == EWORKSPACE
+    assert score(good, q=ctypes.c_void_p(0x1004)) == EALIGN
+    assert score(_shape(P, d=96).c()) == EUNSUPPORTED
+    assert score(_shape(P, block=256).c()) == EUNSUPPORTED
+    assert score(_shape(P, n=0).c()) == EINVAL
+    assert score(_shape(P, stride_n=100).c()) == EINVAL
+    assert score(_shape(P, stride_n=132).c()) == EALIGN
+    assert score(_shape(P, scale=-1.0).c()) == EINVAL
+
+    def route(scores=fake, bh=2, nb=16, k=4, amp=0.1, idx=fake):
+        return L.pasa_route(scores, bh, nb, k, 7, ctypes.c_float(amp), idx, None, None)
+
+
+    assert route(scores=None) == EINVAL
+    assert route(k=0) == EINVAL and route(k=17) == EINVAL
+    assert route(amp=-1.0) == EINVAL and route(amp=float("inf")) == EINVAL
+    assert route(nb=1 << 20, k=4) == EUNSUPPORTED
+
+    def sparse(shape, q=fake, idx=fake, mask=fake, k=4, out=ctypes.c_void_p(0x2000), ws=fake, nbytes=big):
+        return L.pasa_sparse_attn_fwd(q, fake, fake, ctypes.byref(shape), idx, mask, k, out, None, ws, nbytes, None)
+
+    assert sparse(good, idx=None) == EINVAL
+    assert sparse(good, mask=None) == EINVAL
+    assert sparse(good, k=0) == EINVAL and sparse(good, k=129) == EINVAL
+    assert sparse(good, out=fake) == EINVAL  # output aliases an input
+    assert sparse(good, nbytes=ctypes.c_size_t(0)) == EWORKSPACE
+    assert sparse(_shape(P, group=48).c()) == EUNSUPPORTED
+    assert sparse(_shape(P, group=-1).c()) == EINVAL
+    assert sparse(_shape(P, kv_slices=12).c()) == EUNSUPPORTED
+    assert L.pasa_attn_dense_ref(fake, fake, fake, ctypes.byref(good), None, None, fake, big, None) == EINVAL
+    assert L.pasa_kv_stats(None, fake, ctypes.byref(good), fake, big, None) == EINVAL
+    for code in (0, -1, -2, -3, -4, -5, -99):
+        assert isinstance(L.pasa_strerror(code), bytes) and len(L.pasa_strerror(code)) > 0
+
+
+def test_binding_raises_a_clear_error_when_the_library_is_missing(P, monkeypatch):
+    import paper_2604_12219_amd.pasa as mod
+    monkeypatch.setattr(mod, "_lib", None)
+    monkeypatch.setattr(mod, "_LIB_PATH", "/nonexistent/libpasa_hip.so")
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        mod.load_library()
