@@ -21,7 +21,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
-NOISE_AMP_DEFAULT = 0.05        # logit units; see DESIGN.md "input recipe"
+# HBM-side bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# command (scaled by a plain copy of known size; see profiles/attn_kernel_wan14b-720p_hbm_counters.txt).
+# Measured, not computed here: null for workloads without a committed counter run.
+MEASURED_TRAFFIC_BYTES = {("wan14b-720p", 32): 180.1e9 + 0.774e9}
+NOISE_AMP_DEFAULT = 0.125       # logit units: calibrated once on the 480p workload (~15 % of selections change)
 
 
 def algorithmic_flops(B, H, n, d, block, group, k_sel):
@@ -49,16 +53,16 @@ def cpu_baseline(w, q, k, v, k_sel, noise_amp, group, target_seconds=20.0):
     s = oracle.block_scores(q0, k0, w.block).astype(np.float32)
     idx = oracle.route(s, k_sel, w.seed, noise_amp)
     t_route = time.perf_counter() - t0
-    # calibrate on 2 query blocks, then size the sample
-    t0 = time.perf_counter()
-    oracle.pasa_attention(q0, k0, v0, idx, w.block, group=group, q_blocks=[0, nb // 2])
-    t_probe = time.perf_counter() - t0
+    # time the head's statistics alone, probe a few query blocks, then size the sample to the time target
     t0 = time.perf_counter()
     oracle.kv_stats(k0, v0, w.block, group)
     t_stats = time.perf_counter() - t0
-    per_block = max((t_probe - t_stats) / 2, 1e-4)
+    probe = list(range(0, nb, max(1, nb // 16)))[:16]
+    t0 = time.perf_counter()
+    oracle.pasa_attention(q0, k0, v0, idx, w.block, group=group, q_blocks=probe)
+    per_block = max((time.perf_counter() - t0 - t_stats) / len(probe), 1e-4)
     n_sample = int(max(2, min(nb, (target_seconds - t_stats) / per_block)))
-    stride = max(1, nb // n_sample)
+    stride = max(1, -(-nb // n_sample))
     blocks = list(range(0, nb, stride))
     if blocks[-1] != nb - 1:
         blocks.append(nb - 1)  # always include the ragged tail block
@@ -86,6 +90,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain device copy of Q (known size) so that hardware byte counters can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (heads would shard across GPUs with no collective); "
@@ -127,6 +133,10 @@ def main():
         P.sparse_attn_fwd(q, k, v, shape, idx, mask, out=out, ws=ws_attn, prepared=True)
         if events: events[4].record()
 
+    if args.copy_probe:  # 2 * q.numel() * 2 bytes of traffic: read Q, write a copy
+        probe = torch.empty_like(q)
+        probe.copy_(q)
+        del probe
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -181,7 +191,8 @@ def main():
         "speedup_vs_dense_ref": (dense_ms / ms_per_step) if dense_ms else None,
         "roofline": {"kernel": "attn_kernel (sparse: exact tiles + grouped approximation)", "bound": "mfma",
                      "achieved": attn_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, args.group)),
                      "avg_launch_ms": attn_ms, "flops_per_launch": fl["attn"]},
         "paper_context": "paper reports end-to-end video latency only (8x H800): PASA 2.19x over dense at Wan 2.1-14B 720p",
     }
