@@ -30,6 +30,7 @@
 // their use; one workgroup barrier per tile.
 #include "pasa_device.hpp"
 #include "pasa_kernels.hpp"
+#include "pasa_mfma_pipes.hpp"
 #include <stdlib.h>
 
 namespace {
@@ -64,41 +65,22 @@ struct WaveState {
   float l;             // this lane's share of the running normaliser
 };
 
-// Per-lane byte offsets of the MFMA operand fetches inside a 64-row LDS tile, computed once: the XOR
-// swizzle makes them lane-dependent, but a multiple of 16 rows added to the first row does not
-// change the swizzle, so these few registers serve every tile kind through immediate offsets.
-typedef __attribute__((address_space(3))) const bf16x8 lds_bf16x8;
+// Per-lane byte offsets of the MFMA operand fetches inside a 64-row LDS tile, computed once.  The XOR
+// swizzle makes them lane-dependent, but the contraction step of a row fragment and the value-column
+// tile of a column fragment enter the address as an XOR with a constant, and a multiple of 16 rows as
+// an added constant (see pasa_mfma_pipes.hpp), so three registers serve every fetch of every tile.
 template <int D>
 struct LaneOffsets {
-  uint32_t k[D / 16];     // row fragment of rows 0..31, step s
-  uint32_t v[D / 32][2];  // column fragment of rows 0..15, value-column tile t; [1]: the rows 8 further down
+  uint32_t k;     // row fragment of rows 0..31, contraction step 0
+  uint32_t v[2];  // column fragment of rows 0..15, value columns 0..31; [1]: the rows 8 further down
   PASA_DEVICE void init(int lane) {
     const int i = lane & 15, half16 = (lane >> 4) & 1, h = lane >> 5;
-#pragma unroll
-    for (int s = 0; s < D / 16; ++s) k[s] = (uint32_t)lds_chunk_off<D>(lane & 31, 2 * s + h);
-#pragma unroll
-    for (int t = 0; t < D / 32; ++t) {
-      const int row = 4 * h + (i >> 2), col = 32 * t + 16 * half16 + 4 * (i & 3);
-      v[t][0] = (uint32_t)(lds_chunk_off<D>(row, col >> 3) + (col & 7) * 2);
-      v[t][1] = (uint32_t)(lds_chunk_off<D>(row + 8, col >> 3) + (col & 7) * 2);
-    }
+    k = (uint32_t)lds_chunk_off<D>(lane & 31, h);
+    const int row = 4 * h + (i >> 2), col = 16 * half16 + 4 * (i & 3);
+    v[0] = (uint32_t)(lds_chunk_off<D>(row, col >> 3) + (col & 7) * 2);
+    v[1] = (uint32_t)(lds_chunk_off<D>(row + 8, col >> 3) + (col & 7) * 2);
   }
 };
-
-// row fragment (see row_frag): rows row0 .. row0+31 of the tile at LDS address `tile`; row0 in {0, 32}
-template <int D>
-PASA_DEVICE bf16x8 row_frag_at(uint32_t tile, const LaneOffsets<D>& lo, int row0, int s) {
-  return *(lds_bf16x8*)(uintptr_t)(tile + lo.k[s] + (uint32_t)(row0 * 2 * D));
-}
-// column fragment (see col_frag): rows row0 .. row0+15 (row0 a multiple of 16), value columns 32t .. 32t+31
-template <int D>
-PASA_DEVICE bf16x8 col_frag_at(uint32_t tile, const LaneOffsets<D>& lo, int row0, int t) {
-  const uint32_t base = tile + (uint32_t)(row0 * 2 * D);
-  s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(base + lo.v[t][0]));
-  s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(uintptr_t)(base + lo.v[t][1]));
-  s16x8 v = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
-  return __builtin_bit_cast(bf16x8, v);
-}
 
 PASA_DEVICE float max3(float a, float b, float c) {
   float r;
@@ -119,24 +101,19 @@ PASA_DEVICE void rescale(WaveState<D>& w, float m_new) {
     for (int r = 0; r < 16; ++r) w.o[t][r] *= corr;
 }
 
-// One 64-key tile: logits, online softmax, P^T fragments.  n_valid = number of valid keys (rows) in
-// the tile, may be <= 0 (nothing valid) or >= 64 (all valid).
+// Online softmax of one 64-key tile whose logits S^T = K Q^T are in s0 (keys 0..31) and s1 (keys 32..63):
+// updates the running maximum and normaliser and leaves the P^T fragments.  n_valid = number of valid
+// keys (rows) in the tile, may be <= 0 (nothing valid) or >= 64 (all valid).
 template <int D>
-PASA_DEVICE void exact_tile_scores(uint32_t tile, const LaneOffsets<D>& lo, WaveState<D>& w, float c, int n_valid,
-                                   int lane, bf16x8 (&pf)[4]) {
-  const int h = lane >> 5;
-  f32x16 s0 = {0}, s1 = {0};
-#pragma unroll
-  for (int s = 0; s < D / 16; ++s) {
-    s0 = mfma32(row_frag_at<D>(tile, lo, 0, s), w.qf[s], s0);
-    s1 = mfma32(row_frag_at<D>(tile, lo, 32, s), w.qf[s], s1);
-  }
+PASA_DEVICE void exact_tile_softmax(f32x16& s0, f32x16& s1, WaveState<D>& w, float c, int n_valid, int lane,
+                                    bf16x8 (&pf)[4]) {
   if (n_valid < 64) {
+    const int nv = n_valid - 4 * (lane >> 5);  // key 8g + 4h + r is valid iff 8g + r < n_valid - 4h
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      int key = mfma_row(r, h);
-      if (key >= n_valid) s0[r] = -INFINITY;
-      if (key + 32 >= n_valid) s1[r] = -INFINITY;
+      const int key = mfma_row(r, 0);
+      if (key >= nv) s0[r] = -INFINITY;
+      if (key + 32 >= nv) s1[r] = -INFINITY;
     }
   }
   float mx = fmaxf(s0[0], s1[0]);
@@ -162,16 +139,6 @@ PASA_DEVICE void exact_tile_scores(uint32_t tile, const LaneOffsets<D>& lo, Wave
   }
 }
 
-template <int D>
-PASA_DEVICE void exact_tile_pv(uint32_t tile, const LaneOffsets<D>& lo, WaveState<D>& w, const bf16x8 (&pf)[4]) {
-#pragma unroll
-  for (int ks = 0; ks < 4; ++ks) {  // 16 keys per step: rows 16*ks ..
-#pragma unroll
-    for (int t = 0; t < D / 32; ++t) w.o[t] = mfma32(col_frag_at<D>(tile, lo, 16 * ks, t), pf[ks], w.o[t]);
-    if (ks & 1) __builtin_amdgcn_sched_barrier(0);  // keep the operand fetches of at most two steps in flight
-  }
-}
-
 // Zeroth-order part of one chunk of 32 key blocks (Eq.4).  Rows 0..31 of the statistics tile hold
 // the block-mean keys, rows 32..63 the block value sums.  `word` has bit x set iff block
 // 32*chunk + x is selected; blocks at or beyond nb do not exist.  On return a[r] = a_j of the block
@@ -180,15 +147,14 @@ template <int D>
 PASA_DEVICE void approx_chunk_zeroth(uint32_t tile, const LaneOffsets<D>& lo, WaveState<D>& w, float c, uint32_t word,
                                      int chunk, int nb, int block, int tail, int lane, f32x16& a) {
   const int h = lane >> 5;
-  f32x16 z = {0};
-#pragma unroll
-  for (int s = 0; s < D / 16; ++s) z = mfma32(row_frag_at<D>(tile, lo, 0, s), w.qf[s], z);
+  f32x16 z, z1;
+  pipes::rows32_x_q(tile + lo.k, w.qf, z, z1);
   float mx = -INFINITY;
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     int x = mfma_row(r, h), j = 32 * chunk + x;
     bool unsel = (j < nb) && !((word >> x) & 1u);
-    z[r] = unsel ? z[r] : -INFINITY;
+    z[r] = unsel ? z[r] + z1[r] : -INFINITY;
     mx = fmaxf(mx, z[r]);
   }
   mx = half_swap_max(mx) * c;
@@ -208,27 +174,19 @@ PASA_DEVICE void approx_chunk_zeroth(uint32_t tile, const LaneOffsets<D>& lo, Wa
     pf[0][i] = (__bf16)z[i];
     pf[1][i] = (__bf16)z[8 + i];
   }
-#pragma unroll
-  for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-    for (int t = 0; t < D / 32; ++t)
-      w.o[t] = mfma32(col_frag_at<D>(tile, lo, 32 + 16 * ks, t), pf[ks], w.o[t]);
+  pipes::cols_x_p32_hi(tile + lo.v[0], tile + lo.v[1], pf, w.o);
   a = z;
 }
 
 // First-order term of one group (Eq.14), 64 value columns at a time: O^T[part] += ((scale Hg)^T Q^T) diag(A),
-// A = sum of the chunk's a_j over the unselected blocks of the group.  h_lds holds rows
+// A = sum of the chunk's a_j over the unselected blocks of the group.  The tile holds rows
 // [64*part, 64*part + 64) of (scale Hg)^T as a K-like tile (row = value column, col = key column).
 template <int D, int PART>
 PASA_DEVICE void first_order_part(uint32_t tile, const LaneOffsets<D>& lo, WaveState<D>& w, float A) {
   // q~ Hg for this lane's query (a lane owns one query, so its group weight A is a per-lane scalar
   // that multiplies the finished product)
-  f32x16 w0 = {0}, w1 = {0};
-#pragma unroll
-  for (int s = 0; s < D / 16; ++s) {
-    w0 = mfma32(row_frag_at<D>(tile, lo, 0, s), w.qf[s], w0);
-    w1 = mfma32(row_frag_at<D>(tile, lo, 32, s), w.qf[s], w1);
-  }
+  f32x16 w0, w1;
+  pipes::rows_x_q(tile + lo.k, w.qf, w0, w1);
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     w.o[2 * PART][r] = fmaf(A, w0[r], w.o[2 * PART][r]);
@@ -397,6 +355,11 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
     if (q_row < n && !(kDebugModes && p.debug_mode == 4)) raw = *reinterpret_cast<const uint4*>(qb + (int64_t)q_row * p.stride_n + 16 * s + 8 * h);
     w.qf[s] = __builtin_bit_cast(bf16x8, raw);
   }
+  // Have the query loads land here.  Otherwise the compiler, which cannot see the tile loads written in
+  // assembly, waits for "all loads" at the first use of Q inside the tile loop, in every iteration, and
+  // so also for the tiles that were requested just before -- the prefetch would never overlap the math.
+#pragma unroll
+  for (int s = 0; s < D / 16; ++s) asm volatile("" : "+v"(w.qf[s]));
 #pragma unroll
   for (int t = 0; t < D / 32; ++t) w.o[t] = f32x16{0};
   w.m = -INFINITY;
@@ -519,6 +482,8 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
   // While a pair is being consumed the next pair (or the head of the approximation stream) is on its
   // way into the other two ring slots.
   uint32_t prof[6] = {0, 0, 0, 0, 0, 0};  // cycles: wait, scores, produce, PV; steps mine, steps not mine
+  const uint64_t wg_t0 = kProfile ? __builtin_amdgcn_s_memtime() : 0ull;
+  const uint64_t wg_r0 = kProfile ? __builtin_amdgcn_s_memrealtime() : 0ull;
   uint32_t dk = produce_pair();
   if (dk == kEnd) { d0 = produce_approx(); d1 = produce_approx(); }
 #pragma unroll 1
@@ -532,9 +497,13 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
     if (dk == kEnd) { d0 = produce_approx(); d1 = produce_approx(); }
     const bool mine = qb_exists && ((cur >> (second ? 4 : 3)) & 1u) && !(kDebugModes && p.debug_mode == 2);
     const uint32_t t1 = kProfile ? clock32() : 0u;
-    if (mine) exact_tile_scores<D>(slot(it), lo, w, p.c, (int)((cur >> 5) & 127u), lane, pf);
+    if (mine) {
+      f32x16 s0, s1;
+      pipes::rows_x_q(slot(it) + lo.k, w.qf, s0, s1);
+      exact_tile_softmax<D>(s0, s1, w, p.c, (int)((cur >> 5) & 127u), lane, pf);
+    }
     const uint32_t t2 = kProfile ? clock32() : 0u;
-    if (mine) exact_tile_pv<D>(slot(it + 1), lo, w, pf);
+    if (mine) pipes::cols_x_p64(slot(it + 1) + lo.v[0], slot(it + 1) + lo.v[1], pf, w.o);
     it += 2;
     if (kProfile) {
       const uint32_t t4 = clock32();
@@ -544,6 +513,8 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
   }
   if (kProfile && p.prof && lane == 0) {
     for (int x = 0; x < 6; ++x) atomicAdd(p.prof + wave * 8 + x, (unsigned long long)prof[x]);
+    atomicAdd(p.prof + wave * 8 + 6, (unsigned long long)(__builtin_amdgcn_s_memtime() - wg_t0));
+    atomicAdd(p.prof + wave * 8 + 7, (unsigned long long)(__builtin_amdgcn_s_memrealtime() - wg_r0));
   }
 
   // Moves on to the next tile of the approximation stream: waits for it, meets the other waves (after
