@@ -4,7 +4,7 @@
 Why generated assembly: the operand fetches of an MFMA chain have to be requested several MFMAs ahead of
 their use (an LDS read takes longer than an MFMA), which needs a fixed set of operand buffers and counted
 waits.  Each sequence is ONE asm statement, so nothing can be scheduled into it and no register of it can
-be copied or reused while a read is in flight.  The operand buffers are fixed registers (v216..v255,
+be copied or reused while a read is in flight.  The operand buffers are fixed registers (v226..v255,
 declared as clobbered): a transposing read fills half of an MFMA operand, and inline-asm operands cannot
 name half of a register tuple.
 
@@ -18,9 +18,9 @@ every per-fetch address computation.
 """
 import os
 
-FBASE = 224            # operand buffers: 8 x 4 registers v[224:255]
-TBASE = 216            # address temporaries v216..v223
-CLOBBER_LO, CLOBBER_HI = 216, 255
+FBASE = 232            # operand buffers: 6 x 4 registers v[232:255]
+TBASE = 226            # address temporaries v226..v231
+CLOBBER_LO, CLOBBER_HI = 226, 255
 MFMA = "v_mfma_f32_32x32x16_bf16"
 NOP_AFTER = "s_nop 13"  # an 8-pass MFMA result may be read by a VALU instruction 12 wait states later
 
@@ -59,7 +59,7 @@ def rows_x_q(D, two_halves, dma):
             frags.append((s, half_off, "c1"))
         else:
             frags.append((s, 0, "c0" if s % 2 == 0 else "c1"))
-    nbuf = 8
+    nbuf = 6
     lines = []
     last = {"s": 0, "reg": "%[a]", "n": 0}
 
@@ -110,11 +110,11 @@ def cols_x_p(D, nks, row0, dma=0):
     nbuf = 6
     lines = []
     for t in range(1, nt):  # addresses for t >= 1
-        lines.append(f"v_xor_b32 {T(2 * t)}, {hex(t << 6)}, %[a0]")
-        lines.append(f"v_xor_b32 {T(2 * t + 1)}, {hex(t << 6)}, %[a1]")
+        lines.append(f"v_xor_b32 {T(2 * t - 2)}, {hex(t << 6)}, %[a0]")
+        lines.append(f"v_xor_b32 {T(2 * t - 1)}, {hex(t << 6)}, %[a1]")
 
     def a(t, j):
-        return (f"%[a{j}]") if t == 0 else T(2 * t + j)
+        return (f"%[a{j}]") if t == 0 else T(2 * t - 2 + j)
 
     def issue(i):
         ks, t = frags[i]
@@ -158,7 +158,7 @@ def q_inputs(D):
 def gen():
     out = []
     out.append("// GENERATED by gen_mfma_pipes.py -- do not edit.  Software-pipelined LDS-read + MFMA sequences of the\n"
-               "// attention kernel (gfx950).  Every function is one asm statement; v216..v255 are its operand buffers.\n"
+               "// attention kernel (gfx950).  Every function is one asm statement; v226..v255 are its operand buffers.\n"
                "#pragma once\n#include \"pasa_device.hpp\"\n\nnamespace pipes {\n")
     for D in (128, 64):
         ni = (64 // (1024 // (2 * D))) // 4

@@ -31,7 +31,6 @@
 #include "pasa_device.hpp"
 #include "pasa_kernels.hpp"
 #include "pasa_mfma_pipes.hpp"
-#include <stdlib.h>
 
 namespace {
 
@@ -42,13 +41,8 @@ constexpr int kWaves = 4;   // waves per workgroup
 constexpr int kRing = 4;    // LDS tile buffers
 constexpr int kAhead = 3;   // a tile is requested this many tiles before it is consumed
 constexpr int kNoBlock = 0x7fffffff;
-#ifdef PASA_DEBUG_MODES
-constexpr bool kDebugModes = true;   // timing experiments: results are wrong on purpose
-#else
-constexpr bool kDebugModes = false;
-#endif
 #ifdef PASA_PROFILE_PHASES
-constexpr bool kProfile = true;      // per-phase cycle counts of the exact loop into AttnParams::prof
+constexpr bool kProfile = true;      // per-phase cycle counts into AttnParams::prof
 #else
 constexpr bool kProfile = false;
 #endif
@@ -102,18 +96,20 @@ PASA_DEVICE void rescale(WaveState<D>& w, float m_new) {
 }
 
 // Online softmax of one 64-key tile whose logits S^T = K Q^T are in s0 (keys 0..31) and s1 (keys 32..63):
-// updates the running maximum and normaliser and leaves the P^T fragments.  n_valid = number of valid
-// keys (rows) in the tile, may be <= 0 (nothing valid) or >= 64 (all valid).
+// updates the running maximum and normaliser and leaves the P^T fragments.  Only the tile rows
+// [first, end) count as keys (a tile that would reach beyond the last token is fetched shifted back, so
+// its leading rows belong to the tile before it; see the tile requests in the kernel).  The window
+// may be empty.
 template <int D>
-PASA_DEVICE void exact_tile_softmax(f32x16& s0, f32x16& s1, WaveState<D>& w, float c, int n_valid, int lane,
+PASA_DEVICE void exact_tile_softmax(f32x16& s0, f32x16& s1, WaveState<D>& w, float c, int first, int end, int lane,
                                     bf16x8 (&pf)[4]) {
-  if (n_valid < 64) {
-    const int nv = n_valid - 4 * (lane >> 5);  // key 8g + 4h + r is valid iff 8g + r < n_valid - 4h
+  if (first > 0 || end < 64) {
+    const int f = first - 4 * (lane >> 5), e = end - 4 * (lane >> 5);  // key = 8g + r + 4h is valid iff f <= 8g + r < e
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int key = mfma_row(r, 0);
-      if (key >= nv) s0[r] = -INFINITY;
-      if (key + 32 >= nv) s1[r] = -INFINITY;
+      if (key < f || key >= e) s0[r] = -INFINITY;
+      if (key + 32 < f || key + 32 >= e) s1[r] = -INFINITY;
     }
   }
   float mx = fmaxf(s0[0], s1[0]);
@@ -121,7 +117,7 @@ PASA_DEVICE void exact_tile_softmax(f32x16& s0, f32x16& s1, WaveState<D>& w, flo
   for (int r = 1; r < 16; ++r) mx = max3(mx, s0[r], s1[r]);
   mx = half_swap_max(mx) * c;
   if (__builtin_amdgcn_ballot_w64(mx > w.m)) rescale<D>(w, fmaxf(w.m, mx));
-  const float neg = -w.m;
+  const float neg = w.m == -INFINITY ? 0.f : -w.m;  // nothing seen yet and nothing valid here: P = exp2(-inf) = 0
   float sum = 0.f;
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
@@ -197,7 +193,8 @@ PASA_DEVICE void first_order_part(uint32_t tile, const LaneOffsets<D>& lo, WaveS
 // ---- direct global -> LDS tile loads ------------------------------------------------------------
 // One instruction moves 1 KB: 64 lanes x 16 bytes land at consecutive LDS addresses starting at M0,
 // i.e. RPI = 1024/(2D) whole tile rows; the XOR swizzle of the LDS layout is applied on the global
-// side (which 16-byte chunk of its row a lane fetches).  Wave w issues instruction slots w, w+4, ...
+// side (which 16-byte chunk of its row a lane fetches).  Wave w issues instructions w, w+4, ... of a
+// tile; a lane's rows in them are a multiple of 16 apart, so its swizzle is the same in all of them.
 // The loads are written as inline assembly so that the compiler's wait-count insertion does not see
 // them (it would serialise every LDS read behind all pending loads); ordering is by the counted
 // waits in ring_barrier().  A wait count the compiler derives for its own loads can only become
@@ -212,36 +209,27 @@ struct TileDma {
   static constexpr int CPR = D / 8;                 // 16-byte chunks per row
   static constexpr int RPI = 1024 / (2 * D);        // rows per instruction
   static constexpr int NI = 64 / RPI / kWaves;      // instructions per wave and tile
-  static_assert((kWaves * RPI) % 16 == 0, "a lane's swizzle must not change between its instructions");
+  static constexpr int STEP = kWaves * RPI;         // a lane's rows in consecutive instructions are this far apart
+  static_assert(STEP % 16 == 0, "a lane's swizzle must be the same in all of its instructions");
 
-  PASA_DEVICE static int tile_row(int i, int wave, int lane) { return (i * kWaves + wave) * RPI + lane / CPR; }
-  PASA_DEVICE static uint32_t chunk_off(int row, int lane) { return (uint32_t)(((lane % CPR) ^ swz<D>(row)) << 4); }
-
-  // per-lane byte offsets of the lane's chunk in each of the wave's NI instructions, for a given row
-  // stride (a lane's swizzle is the same in all of them; the rows are kWaves*RPI apart)
-  PASA_DEVICE static void lane_offsets(int64_t stride_elems, int wave, int lane, uint32_t (&voff)[NI]) {
-#pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      const int r = tile_row(i, wave, lane);
-      voff[i] = (uint32_t)(r * stride_elems * 2) + chunk_off(r, lane);
-    }
+  int row0;       // the lane's row in the wave's first instruction
+  uint32_t coff;  // byte offset of the lane's (swizzled) chunk inside its row
+  PASA_DEVICE void init(int wave, int lane) {
+    row0 = wave * RPI + lane / CPR;
+    coff = (uint32_t)(((lane % CPR) ^ swz<D>(row0)) << 4);
   }
-  // all 64 rows are in bounds.  base: wave-uniform address of the tile's first row; lds_wave: LDS
-  // address of the slot plus wave*1024.
-  PASA_DEVICE static void issue(const void* base, const uint32_t (&voff)[NI], uint32_t lds_wave) {
+  // Per-lane byte offsets of the wave's NI loads of a tile, relative to the tile's first row.  Rows are
+  // clamped to n_rows - 1: a no-op for a matrix of at least 64 rows (tiles are requested such that
+  // they lie inside it), and for a shorter one the rows that do not exist re-read the last row.
+  PASA_DEVICE void offsets(uint32_t row_bytes, int n_rows, uint32_t (&x)[NI]) const {
 #pragma unroll
-    for (int i = 0; i < NI; ++i) dma_1k(base, voff[i], lds_wave + (uint32_t)(i * kWaves * 1024));
+    for (int i = 0; i < NI; ++i) x[i] = (uint32_t)min(row0 + STEP * i, n_rows - 1) * row_bytes + coff;
   }
-  // tile rows at or beyond `valid` (>= 1) re-read row valid-1 of the tile (finite stand-ins for rows
-  // that do not exist; the caller masks them out).
-  PASA_DEVICE static void issue_clamped(const uint16_t* base, int64_t stride_elems, int valid, uint32_t lds, int wave,
-                                        int lane) {
+  // Requests this wave's share of the tile whose first row is at `base` (wave-uniform).
+  // lds_wave: LDS address of the slot plus wave*1024.
+  PASA_DEVICE static void request(const void* base, const uint32_t (&x)[NI], uint32_t lds_wave) {
 #pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      const int r = tile_row(i, wave, lane);
-      const uint32_t voff = (uint32_t)(min(r, valid - 1) * stride_elems * 2) + chunk_off(r, lane);
-      dma_1k(base, voff, lds + (uint32_t)((i * kWaves + wave) * 1024));
-    }
+    for (int i = 0; i < NI; ++i) dma_1k(base, x[i], lds_wave + (uint32_t)(i * kWaves * 1024));
   }
 };
 
@@ -256,35 +244,49 @@ PASA_DEVICE void ring_barrier(int newer) {
   else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-// ---- the ascending walk over the union of (up to) two block lists --------------------------------
-struct UnionWalk {
-  const_i32* la;
-  const_i32* lb;
-  int k_a, k_b;        // list lengths (0 = list absent)
-  int ia, ib, va, vb;  // cursors and the block ids under them (kNoBlock when exhausted)
-  int sub;             // 64-key tile within the current block
-  PASA_DEVICE void init(const_i32* a, int ka, const_i32* b, int kb) {
-    la = a; lb = b; k_a = ka; k_b = kb; ia = ib = sub = 0;
-    va = ka > 0 ? a[0] : kNoBlock;
-    vb = kb > 0 ? b[0] : kNoBlock;
+// ---- walking a selection bitmap ------------------------------------------------------------------
+// Yields, in ascending order, the key blocks whose bit is set in a combination of (up to) two bitmap
+// rows, within a range of 32-bit words.  MODE 0: blocks in both rows; 1: in row a only; 2: in row b
+// only; 3: row a as it is.  All state is wave-uniform; the word after the current one is requested
+// one word early so that the scalar load is off the critical path.
+template <int MODE>
+struct BitWalk {
+  const_u32* ra;
+  const_u32* rb;
+  int wi, w_end;
+  uint32_t cur, nxt;
+  PASA_DEVICE uint32_t word(int i) const {
+    const uint32_t a = ra[i];
+    if constexpr (MODE == 3) return a;
+    const uint32_t b = rb[i];
+    return MODE == 0 ? (a & b) : MODE == 1 ? (a & ~b) : (b & ~a);
   }
-  PASA_DEVICE bool done() const { return va == kNoBlock && vb == kNoBlock; }
-  PASA_DEVICE int block() const { return min(va, vb); }  // current block id
-  PASA_DEVICE bool in_a() const { return va <= vb; }      // ... and which lists contain it
-  PASA_DEVICE bool in_b() const { return vb <= va; }
-  PASA_DEVICE void advance(int tiles_per_block) {
-    if (++sub < tiles_per_block) return;
-    sub = 0;
-    const int j = min(va, vb);
-    if (va == j) { ++ia; va = ia < k_a ? la[ia] : kNoBlock; }
-    if (vb == j) { ++ib; vb = ib < k_b ? lb[ib] : kNoBlock; }
+  PASA_DEVICE void init(const_u32* a, const_u32* b, int w0, int w1) {
+    ra = a; rb = b; wi = w0; w_end = w1;
+    cur = w0 < w1 ? word(w0) : 0u;
+    nxt = w0 + 1 < w1 ? word(w0 + 1) : 0u;
+  }
+  PASA_DEVICE int next() {  // kNoBlock when exhausted (and on every later call)
+    while (cur == 0u) {
+      if (wi + 1 >= w_end) return kNoBlock;
+      ++wi;
+      cur = nxt;
+      nxt = wi + 1 < w_end ? word(wi + 1) : 0u;
+    }
+    const int j = __builtin_ctz(cur);
+    cur &= cur - 1u;
+    return 32 * wi + j;
   }
 };
 
-// MULTI: the group has fewer than 32 blocks, so a chunk of 32 blocks intersects several groups and
-// the per-block weights of a chunk have to be kept until all of its group matrices have passed.
-template <int D, bool SPARSE, bool MULTI>
+// Kernel variants.  MODE 0: dense (every tile); 1: sparse, one 128-token query block per workgroup;
+// 2: sparse, two adjacent 64-token query blocks per workgroup.  MULTI: the group has fewer than 32
+// blocks, so a chunk of 32 blocks intersects several groups and the per-block weights of a chunk have
+// to be kept until all of its group matrices have passed.  SLICED: key-range slicing (persistent
+// workgroups, partial results).
+template <int D, int MODE, bool MULTI, bool SLICED>
 __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
+  constexpr bool SPARSE = MODE != 0;
   constexpr int TILE_BYTES = 64 * 2 * D;
   constexpr int NI = TileDma<D>::NI;
   constexpr int HPARTS = D / 64;  // 64-row tiles per group matrix
@@ -297,16 +299,16 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
   const uint32_t ring_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)ring;
   LaneOffsets<D> lo;
   lo.init(lane);
-  uint32_t voff_kv[NI], voff_ws[NI];  // lane offsets of the tile loads: rows of K/V (caller's stride), workspace tiles
-  TileDma<D>::lane_offsets(p.stride_n, wave, lane, voff_kv);
-  TileDma<D>::lane_offsets(D, wave, lane, voff_ws);
-  const uint32_t ring_wave = ring_base + (uint32_t)(wave * 1024);
+  TileDma<D> dma;
+  dma.init(wave, lane);
   const uint32_t row_bytes = (uint32_t)(p.stride_n * 2);
-  int issued = 0;  // tiles requested so far; tile i goes to ring slot i & 3 (keeps counting across work items)
-  int it = 0;      // tiles consumed so far
-  const bool persistent = p.n_slices > 1;
+  uint32_t x_kv[NI];  // lane offsets of the loads of a whole K or V tile
+  dma.offsets(row_bytes, p.n, x_kv);
+  const uint32_t ring_wave = ring_base + (uint32_t)(wave * 1024);
+  auto slot = [&](int i) -> uint32_t { return ring_base + (uint32_t)((i & (kRing - 1)) * TILE_BYTES); };
+  auto slot_wave = [&](int i) -> uint32_t { return ring_wave + (uint32_t)((i & (kRing - 1)) * TILE_BYTES); };
   int xcd = blockIdx.x % kXcds;
-  if (persistent) {  // ask the hardware which XCD this workgroup really runs on
+  if constexpr (SLICED) {  // ask the hardware which XCD this workgroup really runs on
     unsigned id;
     asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(id));
     xcd = (int)(id & 15u) % kXcds;
@@ -323,10 +325,10 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
   // the dispatch to all the others.)
   for (;;) {
   int bh, qt, slice = 0;
-  if (persistent) {
+  if constexpr (SLICED) {
     if (tid == 0) s_item = (int)atomicAdd(p.queue + xcd, 1u);
     __syncthreads();
-    const int item = s_item;
+    const int item = __builtin_amdgcn_readfirstlane(s_item);
     __syncthreads();  // everyone has read s_item before it can be written again
     if (item >= p.items_per_xcd) return;  // queue empty: every wave of the workgroup leaves here
     const int rounds = p.n_slices / kXcds;
@@ -352,11 +354,11 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
 #pragma unroll
   for (int s = 0; s < D / 16; ++s) {
     uint4 raw = {0u, 0u, 0u, 0u};
-    if (q_row < n && !(kDebugModes && p.debug_mode == 4)) raw = *reinterpret_cast<const uint4*>(qb + (int64_t)q_row * p.stride_n + 16 * s + 8 * h);
+    if (q_row < n) raw = *reinterpret_cast<const uint4*>(qb + (int64_t)q_row * p.stride_n + 16 * s + 8 * h);
     w.qf[s] = __builtin_bit_cast(bf16x8, raw);
   }
   // Have the query loads land here.  Otherwise the compiler, which cannot see the tile loads written in
-  // assembly, waits for "all loads" at the first use of Q inside the tile loop, in every iteration, and
+  // assembly, waits for "all loads" at the first use of Q inside the tile loops, in every iteration, and
   // so also for the tiles that were requested just before -- the prefetch would never overlap the math.
 #pragma unroll
   for (int s = 0; s < D / 16; ++s) asm volatile("" : "+v"(w.qf[s]));
@@ -365,197 +367,207 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
   w.m = -INFINITY;
   w.l = 0.f;
 
-  // ---- which query block this wave belongs to, and the block lists of the workgroup ----
-  const int qpw = SPARSE ? 128 / p.block : 1;             // query blocks per workgroup: 1 or 2
-  const bool second = SPARSE && qpw == 2 && (wave >> 1);  // this wave works for the second list
-  const int my_qb = SPARSE ? qt * qpw + (second ? 1 : 0) : 0;
-  const bool qb_exists = !SPARSE || my_qb < p.nb;         // the second block of the last pair may not exist
-  const int tiles_per_block = SPARSE ? p.block / 64 : 1;
+  // ---- the selection bitmaps of the workgroup ----
+  // MODE 2: waves 0, 1 work for query block 2 qt (row a of the bitmap), waves 2, 3 for block 2 qt + 1
+  // (row b).  If the last query tile has no second block, row b := row a; waves 2, 3 then repeat the
+  // walk of the first block with all-zero queries (their rows lie beyond n and are never stored).
+  const bool second = MODE == 2 && (wave >> 1);
   const int n_dense_tiles = (n + 63) / 64;
   const bool approx_on = SPARSE && p.group > 0;
   const uint16_t* const st = approx_on ? p.st + (int64_t)bh * p.n_chunks * 64 * D : nullptr;
   const uint16_t* const hg = approx_on ? p.hg + (int64_t)bh * p.n_groups * D * D : nullptr;
-  const_u32* const mask_row =
-      (approx_on && qb_exists) ? (const_u32*)(p.mask + ((int64_t)bh * p.nb + my_qb) * p.mask_words) : nullptr;
-
-  // chunk range of this workgroup's slice, and for each list the entries that fall into it: their
-  // number and the position of the first one are popcounts over the selection bitmap
+  // chunk (= bitmap word) range of this workgroup's key slice
   const int c_lo = SPARSE ? (int)((int64_t)slice * p.n_chunks / p.n_slices) : 0;
   const int c_hi = SPARSE ? (int)((int64_t)(slice + 1) * p.n_chunks / p.n_slices) : 0;
-  int first_a = 0, count_a = SPARSE ? p.k_sel : 0, first_b = 0, count_b = 0;
-  if constexpr (SPARSE) {
-    const bool has_b = qpw == 2 && qt * 2 + 1 < p.nb;
-    count_b = has_b ? p.k_sel : 0;
-    if (p.n_slices > 1) {
-      auto bits_in = [&](const uint32_t* row, int w0, int w1) -> int {  // wave-uniform result
-        int acc = 0;
-        for (int x = w0 + lane; x < w1; x += 64) acc += __popc(row[x]);
-#pragma unroll
-        for (int sh = 32; sh >= 1; sh >>= 1) acc += __shfl_xor(acc, sh);
-        return __builtin_amdgcn_readfirstlane(acc);
-      };
-      const uint32_t* ma = p.mask + ((int64_t)bh * p.nb + (int64_t)qt * qpw) * p.mask_words;
-      first_a = bits_in(ma, 0, c_lo);
-      count_a = bits_in(ma, c_lo, c_hi);
-      if (has_b) {
-        first_b = bits_in(ma + p.mask_words, 0, c_lo);
-        count_b = bits_in(ma + p.mask_words, c_lo, c_hi);
-      }
-    }
-  }
-  auto make_walk = [&]() {
-    UnionWalk u;
+  const int qb_a = MODE == 2 ? 2 * qt : qt;
+  const_u32* const mask_a = SPARSE ? (const_u32*)(p.mask + ((int64_t)bh * p.nb + qb_a) * p.mask_words) : nullptr;
+  const_u32* const mask_b = (MODE == 2 && qb_a + 1 < p.nb) ? mask_a + p.mask_words : mask_a;
+  const_u32* const mask_row = second ? mask_b : mask_a;  // this wave's own row
+
+  // Tile requests.  The tile for key rows [r0, r0 + 64) is fetched from row tile_row(r0) on: shifted
+  // back where it would reach beyond the last token, so that all 64 rows exist (r0 may even lie beyond
+  // n: the second tile of the last 128-token block).  The consumer ignores the rows before r0.  Every
+  // request has the same form, either here or in the shadow of MFMAs (the *_dma sequences).
+  auto tile_row = [&](int r0) -> int { return max(min(r0, n - 64), 0); };
+  auto tile_ptr = [&](const uint16_t* base, int r0) -> const char* {
+    return reinterpret_cast<const char*>(base) + (uint32_t)tile_row(r0) * row_bytes;
+  };
+  auto request = [&](const uint16_t* base, int r0, int sl) { TileDma<D>::request(tile_ptr(base, r0), x_kv, slot_wave(sl)); };
+
+  uint32_t prof[8] = {0, 0, 0, 0, 0, 0, 0, 0};  // cycles: part 1 barrier, logits+softmax, PV; part 2; steps part 1, part 2; approximation; item
+  const uint32_t t_item = kProfile ? clock32() : 0u;
+
+  // ---------------- exact attention, part 1: tiles that all four waves need ----------------
+  // (every tile of the dense path; the blocks of a 128-token query block; with two 64-token query
+  // blocks the key blocks that BOTH selected).  One barrier per (K tile, V tile) pair; while a pair is
+  // consumed the next pair is on its way into the other two ring slots, requested in the shadow of
+  // the first MFMAs.  The order in which key blocks are visited does not matter to an online softmax.
+  {
+    BitWalk<MODE == 2 ? 0 : 3> walk;
+    int blk = kNoBlock, sub = 0, dense_next = 0;
     if constexpr (SPARSE) {
-      const_i32* base = (const_i32*)(p.idx + ((int64_t)bh * p.nb + (int64_t)qt * qpw) * p.k_sel);
-      u.init(base + first_a, count_a, base + p.k_sel + first_b, count_b);
-    } else {
-      u.init(nullptr, 0, nullptr, 0);
+      walk.init(mask_a, mask_b, c_lo, c_hi);
+      blk = walk.next();
     }
-    return u;
-  };
-  auto first_group = [&](int chunk) { return (32 * chunk) / p.group; };
-  auto last_group = [&](int chunk) { return (min(32 * chunk + 32, p.nb) - 1) / p.group; };
-
-  // ---- the producers.  A tile that is requested goes to ring slot `issued & 3`; the consumer learns what it
-  // is from a descriptor:
-  //   bits 0-2 kind; bit 3 / bit 4: the block is in the first / second list;
-  //   K tiles:           bits 5-11  number of valid rows, clamped to [0, 64]  (its V tile follows it)
-  //   statistics, Hg:    bits 5-12  chunk, bits 14-25 group
-  enum : uint32_t { kEnd = 0, kKTile = 1, kStats = 3, kHPart = 4 };
-  auto slot = [&](int i) -> uint32_t { return ring_base + (uint32_t)((i & (kRing - 1)) * TILE_BYTES); };
-  auto slot_wave = [&](int i) -> uint32_t { return ring_wave + (uint32_t)((i & (kRing - 1)) * TILE_BYTES); };
-
-  // exact phase: requests the K tile and the V tile of the next step of the walk into the next two slots
-  UnionWalk pw = make_walk();
-  int p_dense = 0;  // dense: next tile
-  auto produce_pair = [&]() -> uint32_t {
-    if (SPARSE ? pw.done() : (p_dense >= n_dense_tiles)) return kEnd;
-    if (kDebugModes && p.debug_mode == 1 && issued >= 2) { issued += 2; if constexpr (SPARSE) pw.advance(tiles_per_block); else ++p_dense; return kKTile | 8u | 16u | (64u << 5); }
-    const int r0 = SPARSE ? pw.block() * p.block + pw.sub * 64 : p_dense * 64;
-    const int valid = n - r0;
-    uint32_t desc = kKTile | ((uint32_t)min(max(valid, 0), 64) << 5);
-    if constexpr (SPARSE) desc |= (pw.in_a() ? 8u : 0u) | (pw.in_b() ? 16u : 0u);
-    else desc |= 8u;
-    if (valid >= 64) {
-      const uint32_t off = (uint32_t)r0 * row_bytes;
-      TileDma<D>::issue(reinterpret_cast<const char*>(kb) + off, voff_kv, slot_wave(issued));
-      TileDma<D>::issue(reinterpret_cast<const char*>(vb) + off, voff_kv, slot_wave(issued + 1));
-    } else {  // the ragged last tile, or the tile after it in a 128-token block: rows past the end re-read the last row
-      const int rr = valid >= 1 ? r0 : n - 1, vv = valid >= 1 ? valid : 1;
-      TileDma<D>::issue_clamped(kb + (int64_t)rr * p.stride_n, p.stride_n, vv, slot(issued), wave, lane);
-      TileDma<D>::issue_clamped(vb + (int64_t)rr * p.stride_n, p.stride_n, vv, slot(issued + 1), wave, lane);
-    }
-    issued += 2;
-    if constexpr (SPARSE) pw.advance(tiles_per_block);
-    else ++p_dense;
-    return desc;
-  };
-
-  // approximation phase: requests the next tile: per chunk its statistics tile, then the HPARTS tiles of
-  // every group matrix the chunk intersects
-  const int c_end = approx_on ? c_hi : 0;        // chunks [c_lo, c_end) are approximated by this workgroup
-  int p_chunk = c_lo, p_group = 0, p_part = -1;  // p_part == -1: statistics tile next
-  auto produce_approx = [&]() -> uint32_t {
-    if (p_chunk >= c_end) return kEnd;
-    uint32_t desc;
-    if (p_part < 0) {
-      TileDma<D>::issue(st + (int64_t)p_chunk * 64 * D, voff_ws, slot_wave(issued));
-      desc = kStats | ((uint32_t)p_chunk << 5);
-      p_group = first_group(p_chunk);
-      p_part = 0;
-    } else {
-      TileDma<D>::issue(hg + ((int64_t)p_group * D + 64 * p_part) * D, voff_ws, slot_wave(issued));
-      desc = kHPart | ((uint32_t)p_chunk << 5) | ((uint32_t)p_group << 14);
-      if (++p_part == HPARTS) {
-        p_part = 0;
-        if (++p_group > last_group(p_chunk)) { ++p_chunk; p_part = -1; }
+    auto plan = [&]() -> int {  // first row of the next tile, or -1
+      if constexpr (MODE == 0) {
+        const int t = dense_next++;
+        return t < n_dense_tiles ? t * 64 : -1;
+      } else if constexpr (MODE == 1) {  // two tiles per 128-token block
+        if (blk == kNoBlock) return -1;
+        const int r0 = blk * 128 + sub * 64;
+        if (++sub == 2) { sub = 0; blk = walk.next(); }
+        return r0;
+      } else {
+        if (blk == kNoBlock) return -1;
+        const int r0 = blk * 64;
+        blk = walk.next();
+        return r0;
       }
-    }
-    ++issued;
-    return desc;
-  };
-
-  // ---- the consumer: tile `it` of the stream lives in ring slot it & 3 ----
-  uint32_t d0 = kEnd, d1 = kEnd, d2 = kEnd;  // approximation tiles requested but not yet consumed, in order
-
-  // ---------------- exact tiles: one barrier per (K tile, V tile) pair ----------------
-  // While a pair is being consumed the next pair (or the head of the approximation stream) is on its
-  // way into the other two ring slots.
-  uint32_t prof[6] = {0, 0, 0, 0, 0, 0};  // cycles: wait, scores, produce, PV; steps mine, steps not mine
-  const uint64_t wg_t0 = kProfile ? __builtin_amdgcn_s_memtime() : 0ull;
-  const uint64_t wg_r0 = kProfile ? __builtin_amdgcn_s_memrealtime() : 0ull;
-  uint32_t dk = produce_pair();
-  if (dk == kEnd) { d0 = produce_approx(); d1 = produce_approx(); }
+    };
+    int r_cur = plan();
+    if (r_cur >= 0) { request(kb, r_cur, 0); request(vb, r_cur, 1); }
+    int pair = 0;
 #pragma unroll 1
-  while (dk != kEnd) {
-    bf16x8 pf[4];  // P^T of the tile
-    const uint32_t t0 = kProfile ? clock32() : 0u;
-    ring_barrier<NI>(0);  // the pair has landed; every wave is done with the previous pair
-    const uint32_t tb = kProfile ? clock32() : 0u;
-    const uint32_t cur = dk;
-    dk = produce_pair();
-    if (dk == kEnd) { d0 = produce_approx(); d1 = produce_approx(); }
-    const bool mine = qb_exists && ((cur >> (second ? 4 : 3)) & 1u) && !(kDebugModes && p.debug_mode == 2);
-    const uint32_t t1 = kProfile ? clock32() : 0u;
-    if (mine) {
+    while (r_cur >= 0) {
+      const uint32_t t0 = kProfile ? clock32() : 0u;
+      ring_barrier<NI>(0);  // the pair has landed; every wave is done with the previous pair
+      const uint32_t t1 = kProfile ? clock32() : 0u;
+      const int r_nxt = plan();
+      const uint32_t k_tile = slot(2 * pair), v_tile = slot(2 * pair + 1);
       f32x16 s0, s1;
-      pipes::rows_x_q(slot(it) + lo.k, w.qf, s0, s1);
-      exact_tile_softmax<D>(s0, s1, w, p.c, (int)((cur >> 5) & 127u), lane, pf);
+      bf16x8 pf[4];  // P^T of the tile
+      // the next pair is requested into the other two slots (after the last pair: once more the same, unused)
+      const int r_req = r_nxt >= 0 ? r_nxt : r_cur;
+      pipes::rows_x_q_dma(k_tile + lo.k, w.qf, s0, s1, tile_ptr(kb, r_req), tile_ptr(vb, r_req), x_kv,
+                          slot_wave(2 * pair + 2), slot_wave(2 * pair + 3));
+      exact_tile_softmax<D>(s0, s1, w, p.c, r_cur - tile_row(r_cur), n - tile_row(r_cur), lane, pf);
+      const uint32_t t2 = kProfile ? clock32() : 0u;
+      pipes::cols_x_p64(v_tile + lo.v[0], v_tile + lo.v[1], pf, w.o);
+      if (kProfile) { prof[0] += t1 - t0; prof[1] += t2 - t1; prof[2] += clock32() - t2; prof[4] += 1; }
+      r_cur = r_nxt;
+      ++pair;
     }
-    const uint32_t t2 = kProfile ? clock32() : 0u;
-    if (mine) pipes::cols_x_p64(slot(it + 1) + lo.v[0], slot(it + 1) + lo.v[1], pf, w.o);
-    it += 2;
-    if (kProfile) {
-      const uint32_t t4 = clock32();
-      prof[0] += tb - t0; prof[2] += t1 - tb; prof[1] += t2 - t1; prof[3] += t4 - t2;
-      prof[mine ? 4 : 5] += 1;
-    }
-  }
-  if (kProfile && p.prof && lane == 0) {
-    for (int x = 0; x < 6; ++x) atomicAdd(p.prof + wave * 8 + x, (unsigned long long)prof[x]);
-    atomicAdd(p.prof + wave * 8 + 6, (unsigned long long)(__builtin_amdgcn_s_memtime() - wg_t0));
-    atomicAdd(p.prof + wave * 8 + 7, (unsigned long long)(__builtin_amdgcn_s_memrealtime() - wg_r0));
   }
 
-  // Moves on to the next tile of the approximation stream: waits for it, meets the other waves (after
-  // which the slots of all earlier tiles are free) and tops the ring up to three tiles ahead.
-  // Returns the descriptor of the tile to consume (slot(it)).
-  auto next_tile = [&]() -> uint32_t {
-    const uint32_t cur = d0;
-    ring_barrier<NI>((d1 != kEnd ? 1 : 0) + (d2 != kEnd ? 1 : 0));
-    d0 = d1;
-    d1 = d2;
-    d2 = kEnd;
-    if (d0 == kEnd) d0 = produce_approx();
-    if (d1 == kEnd && d0 != kEnd) d1 = produce_approx();
-    if (d2 == kEnd && d1 != kEnd) d2 = produce_approx();
-    return cur;
-  };
+  // ---------------- exact attention, part 2: key blocks that only one of the two query blocks selected ----------------
+  // Step i handles the i-th such block of the first query block (waves 0, 1; K in slot 0, V in slot 1)
+  // and the i-th of the second (waves 2, 3; slots 2, 3) at the same time, so that no wave idles.  A
+  // buffer cannot be refilled while it is in use, hence two barriers per step: the V tiles of a step
+  // are requested after the first and land during the logits and the softmax, the K tiles of the next
+  // step are requested after the second and land during P V.
+  if constexpr (MODE == 2) {
+    BitWalk<1> only_a;
+    BitWalk<2> only_b;
+    only_a.init(mask_a, mask_b, c_lo, c_hi);
+    only_b.init(mask_a, mask_b, c_lo, c_hi);
+    int a_blk = only_a.next(), b_blk = only_b.next();
+    const uint32_t t0 = kProfile ? clock32() : 0u;
+    if (a_blk != kNoBlock || b_blk != kNoBlock) {
+      ring_barrier<NI>(0);  // every wave is done with the ring
+      request(kb, (a_blk != kNoBlock ? a_blk : b_blk) * 64, 0);
+      request(kb, (b_blk != kNoBlock ? b_blk : a_blk) * 64, 2);
+#pragma unroll 1
+      do {
+        ring_barrier<NI>(0);  // the K tiles have landed; the V slots are free
+        // With key-range slicing one of the two query blocks can run out of blocks before the other.
+        // Its waves then go through the motions on the other block's tiles with an empty key window
+        // (all weights zero), and the missing tile requests repeat the other block's: one code path.
+        const bool have_a = a_blk != kNoBlock, have_b = b_blk != kNoBlock;
+        const int my_blk = second ? b_blk : a_blk;
+        const bool read_b = second ? have_b : !have_a;  // whose slots this wave reads
+        const uint32_t k_tile = slot(read_b ? 2 : 0), v_tile = slot(read_b ? 3 : 1);
+        const int a_req = have_a ? a_blk : b_blk, b_req = have_b ? b_blk : a_blk;
+        const int a_nxt = have_a ? only_a.next() : kNoBlock;
+        const int b_nxt = have_b ? only_b.next() : kNoBlock;
+        const int a_rq2 = a_nxt != kNoBlock ? a_nxt : b_nxt != kNoBlock ? b_nxt : a_req;
+        const int b_rq2 = b_nxt != kNoBlock ? b_nxt : a_rq2;
+        const int t_row = my_blk != kNoBlock ? tile_row(my_blk * 64) : 0;
+        const int first = my_blk != kNoBlock ? my_blk * 64 - t_row : 64, end = my_blk != kNoBlock ? n - t_row : 64;
+        f32x16 s0, s1;
+        bf16x8 pf[4];
+        pipes::rows_x_q_dma(k_tile + lo.k, w.qf, s0, s1, tile_ptr(vb, a_req * 64), tile_ptr(vb, b_req * 64), x_kv,
+                            slot_wave(1), slot_wave(3));
+        exact_tile_softmax<D>(s0, s1, w, p.c, first, end, lane, pf);
+        ring_barrier<NI>(0);  // the V tiles have landed; the K slots are free
+        pipes::cols_x_p64_dma(v_tile + lo.v[0], v_tile + lo.v[1], pf, w.o, tile_ptr(kb, a_rq2 * 64),
+                              tile_ptr(kb, b_rq2 * 64), x_kv, slot_wave(0), slot_wave(2));
+        a_blk = a_nxt;
+        b_blk = b_nxt;
+        if (kProfile) prof[5] += 1;
+      } while (a_blk != kNoBlock || b_blk != kNoBlock);
+    }
+    if (kProfile) prof[3] += clock32() - t0;
+  }
 
   // ---------------- grouped approximation of the unselected blocks ----------------
-  // per chunk of 32 key blocks: its statistics tile, then for every group it intersects the HPARTS
-  // tiles of the group matrix
+  // Per chunk of 32 key blocks: its statistics tile, then for every group it intersects the HPARTS
+  // tiles of the group matrix.  The tiles stream through the ring three ahead of their use, one
+  // barrier per tile; the consumer learns what a tile is from a descriptor:
+  //   bits 0-2 kind;  bits 5-12 chunk;  bits 14-25 group
+  const uint32_t t_approx = kProfile ? clock32() : 0u;
+  if (approx_on && c_lo < c_hi) {
+    enum : uint32_t { kEnd = 0, kStats = 3, kHPart = 4 };
+    ring_barrier<NI>(0);  // every wave is done with the ring
+    int issued = 0;       // tiles requested so far; tile i goes to ring slot i & 3
+    int it = 0;           // tiles consumed so far
+    uint32_t x_ws[NI];  // lane offsets of the loads of a workspace tile (rows of D elements)
+    dma.offsets(2 * D, 64, x_ws);
+    int p_chunk = c_lo, p_group = 0, p_part = -1;  // p_part == -1: statistics tile next
+    auto produce = [&]() -> uint32_t {
+      if (p_chunk >= c_hi) return kEnd;
+      uint32_t desc;
+      const uint16_t* src;
+      if (p_part < 0) {
+        src = st + (int64_t)p_chunk * 64 * D;
+        desc = kStats | ((uint32_t)p_chunk << 5);
+        p_group = (32 * p_chunk) / p.group;
+        p_part = 0;
+      } else {
+        src = hg + ((int64_t)p_group * D + 64 * p_part) * D;
+        desc = kHPart | ((uint32_t)p_chunk << 5) | ((uint32_t)p_group << 14);
+        if (++p_part == HPARTS) {
+          p_part = 0;
+          if (++p_group > (min(32 * p_chunk + 32, p.nb) - 1) / p.group) { ++p_chunk; p_part = -1; }
+        }
+      }
+      TileDma<D>::request(src, x_ws, slot_wave(issued));
+      ++issued;
+      return desc;
+    };
+    uint32_t d0 = produce(), d1 = produce(), d2 = kEnd;  // tiles requested but not yet consumed, in order
+    // Moves on to the next tile of the stream: waits for it, meets the other waves (after which the
+    // slots of all earlier tiles are free) and tops the ring up to three tiles ahead.  Returns the
+    // descriptor of the tile to consume (slot(it)).
+    auto next_tile = [&]() -> uint32_t {
+      const uint32_t cur = d0;
+      ring_barrier<NI>((d1 != kEnd ? 1 : 0) + (d2 != kEnd ? 1 : 0));
+      d0 = d1;
+      d1 = d2;
+      d2 = kEnd;
+      if (d0 == kEnd) d0 = produce();
+      if (d1 == kEnd && d0 != kEnd) d1 = produce();
+      if (d2 == kEnd && d1 != kEnd) d2 = produce();
+      return cur;
+    };
 #pragma unroll 1
-  while (d0 != kEnd) {
-    f32x16 a;  // a_j of the chunk
-    const uint32_t cur = next_tile();
-    const int chunk = (int)((cur >> 5) & 255u);
-    if (qb_exists) approx_chunk_zeroth<D>(slot(it), lo, w, p.c, mask_row[chunk], chunk, p.nb, p.block, p.tail, lane, a);
-    ++it;
-    float A = 0.f;
-    if constexpr (!MULTI) {  // the whole chunk belongs to one group
-      if (qb_exists) {
+    while (d0 != kEnd) {
+      f32x16 a;  // a_j of the chunk
+      const uint32_t cur = next_tile();
+      const int chunk = (int)((cur >> 5) & 255u);
+      approx_chunk_zeroth<D>(slot(it), lo, w, p.c, mask_row[chunk], chunk, p.nb, p.block, p.tail, lane, a);
+      ++it;
+      float A = 0.f;
+      if constexpr (!MULTI) {  // the whole chunk belongs to one group
 #pragma unroll
         for (int r = 0; r < 16; ++r) A += a[r];
         A = half_swap_sum(A);
       }
-    }
 #pragma unroll 1
-    while ((d0 & 7u) == kHPart) {
-      if constexpr (MULTI) {
-        const int g = (int)((d0 >> 14) & 4095u);
-        A = 0.f;
-        if (qb_exists) {
+      while ((d0 & 7u) == kHPart) {
+        if constexpr (MULTI) {
+          const int g = (int)((d0 >> 14) & 4095u);
+          A = 0.f;
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const int j = 32 * chunk + mfma_row(r, h);
@@ -563,22 +575,28 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
           }
           A = half_swap_sum(A);
         }
-      }
-      next_tile();
-      if (qb_exists) first_order_part<D, 0>(slot(it), lo, w, A);
-      ++it;
-      if constexpr (D == 128) {
         next_tile();
-        if (qb_exists) first_order_part<D, 1>(slot(it), lo, w, A);
+        first_order_part<D, 0>(slot(it), lo, w, A);
         ++it;
+        if constexpr (D == 128) {
+          next_tile();
+          first_order_part<D, 1>(slot(it), lo, w, A);
+          ++it;
+        }
       }
     }
+  }
+  if (kProfile && p.prof && lane == 0) {
+    const uint32_t t_end = clock32();
+    prof[6] = t_end - t_approx;
+    prof[7] = t_end - t_item;
+    for (int x = 0; x < 8; ++x) atomicAdd(p.prof + wave * 8 + x, (unsigned long long)prof[x]);
   }
 
   // ---- epilogue ----
   const float l_tot = half_swap_sum(w.l);
-  if (q_row < n && qb_exists && !(kDebugModes && p.debug_mode == 3)) {
-    if (p.n_slices > 1) {  // leave the partial result of this slice to the merge kernel
+  if (q_row < n) {
+    if constexpr (SLICED) {  // leave the partial result of this slice to the merge kernel
       const int64_t prow = ((int64_t)bh * p.n_slices + slice) * n + q_row;
       float* orow = p.part_o + prow * D;
 #pragma unroll
@@ -612,7 +630,9 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
       if (p.lse && h == 0) p.lse[(int64_t)bh * n + q_row] = (w.m + __builtin_amdgcn_logf(l_tot)) * kLn2;
     }
   }
-  if (!persistent) return;
+  if constexpr (!SLICED) return;
+  // the next item's first requests must not overtake the last LDS reads of slower waves
+  ring_barrier<NI>(0);
   }  // next work item
 }
 
@@ -653,20 +673,28 @@ __global__ void __launch_bounds__(256) merge_kernel(AttnParams p) {
   if (p.lse && c4 == 0) p.lse[row] = (M + __builtin_amdgcn_logf(L)) * kLn2;
 }
 
-template <int D, bool SPARSE, bool MULTI>
+template <int D, int MODE, bool MULTI, bool SLICED>
 hipError_t launch(const AttnParams& p, int grid, hipStream_t stream) {
-  hipLaunchKernelGGL((attn_kernel<D, SPARSE, MULTI>), dim3(grid), dim3(kWaves * 64), 0, stream, p);
+  hipLaunchKernelGGL((attn_kernel<D, MODE, MULTI, SLICED>), dim3(grid), dim3(kWaves * 64), 0, stream, p);
   return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_d(const AttnParams& p, bool sparse, int grid, hipStream_t stream) {
+  if (!sparse) return launch<D, 0, false, false>(p, grid, stream);
+  const bool multi = p.group > 0 && p.group < 32, sliced = p.n_slices > 1;
+  if (p.block == 128) {
+    if (sliced) return multi ? launch<D, 1, true, true>(p, grid, stream) : launch<D, 1, false, true>(p, grid, stream);
+    return multi ? launch<D, 1, true, false>(p, grid, stream) : launch<D, 1, false, false>(p, grid, stream);
+  }
+  if (sliced) return multi ? launch<D, 2, true, true>(p, grid, stream) : launch<D, 2, false, true>(p, grid, stream);
+  return multi ? launch<D, 2, true, false>(p, grid, stream) : launch<D, 2, false, false>(p, grid, stream);
 }
 
 }  // namespace
 
 hipError_t pasa_launch_attn(AttnParams p, bool sparse, int d, hipStream_t stream) {
   p.c = p.scale * kLog2e;
-  p.debug_mode = 0;
-#ifdef PASA_DEBUG_MODES
-  if (const char* e = getenv("PASA_DEBUG_MODE")) p.debug_mode = atoi(e);
-#endif
   p.q_tiles = (p.n + 127) / 128;  // 128 query rows per workgroup
   p.q_tiles_per_xcd = (p.q_tiles + kXcds - 1) / kXcds;
   if (!sparse) p.n_slices = 1;
@@ -676,12 +704,7 @@ hipError_t pasa_launch_attn(AttnParams p, bool sparse, int d, hipStream_t stream
     grid = 2 * 256;
     hipLaunchKernelGGL(reset_queue_kernel, dim3(1), dim3(64), 0, stream, p.queue);
   }
-  hipError_t rc = hipErrorInvalidValue;
-  const bool multi = sparse && p.group > 0 && p.group < 32;
-  if (sparse && d == 128) rc = multi ? launch<128, true, true>(p, grid, stream) : launch<128, true, false>(p, grid, stream);
-  else if (sparse && d == 64) rc = multi ? launch<64, true, true>(p, grid, stream) : launch<64, true, false>(p, grid, stream);
-  else if (d == 128) rc = launch<128, false, false>(p, grid, stream);
-  else if (d == 64) rc = launch<64, false, false>(p, grid, stream);
+  const hipError_t rc = d == 128 ? launch_d<128>(p, sparse, grid, stream) : launch_d<64>(p, sparse, grid, stream);
   if (rc != hipSuccess || p.n_slices == 1) return rc;
   const int64_t rows = (int64_t)p.bh * p.n;
   if (d == 128) {

@@ -15,11 +15,10 @@ struct AttnParams {
   int32_t bh, H, n, nb, block, tail;  // tail = valid tokens of the last block
   float scale, c;                     // c = scale * log2(e), filled in by the launcher
   unsigned long long* prof;           // experiments only (PASA_PROFILE_PHASES builds): [4 waves][8] cycle sums
-  int32_t debug_mode;                 // experiments only (PASA_DEBUG_MODES builds): 1 = no tile loads, 2 = no math
   int32_t q_tiles, q_tiles_per_xcd;   // filled in by the launcher
   // sparse path only
-  const int32_t* idx;
-  const uint32_t* mask;
+  const int32_t* idx;    // not read by the attention kernel (it walks the bitmap)
+  const uint32_t* mask;  // [BH][nb][mask_words]: bit j of a row = key block j is selected
   int32_t k_sel, mask_words;
   const uint16_t* st;    // bf16 [BH][n_chunks][64][d]: rows 0..31 block-mean keys, rows 32..63 block value
                          // sums of key blocks 32c..32c+31 (zero rows for blocks that do not exist)
