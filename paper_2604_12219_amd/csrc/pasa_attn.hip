@@ -428,23 +428,36 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
     int r_cur = plan();
     if (r_cur >= 0) { request(kb, r_cur, 0); request(vb, r_cur, 1); }
     int pair = 0;
+    // Tiles whose 64 rows are all keys of the tile: one instruction stream per tile.  (Tiles come in ascending
+    // order, so a tile that reaches beyond the last token can only be among the last ones.)
 #pragma unroll 1
-    while (r_cur >= 0) {
+    while (r_cur >= 0 && r_cur + 64 <= n) {
       const uint32_t t0 = kProfile ? clock32() : 0u;
       ring_barrier<NI>(0);  // the pair has landed; every wave is done with the previous pair
       const uint32_t t1 = kProfile ? clock32() : 0u;
       const int r_nxt = plan();
+      // the next pair is requested into the other two slots (after the last pair: once more the same, unused)
+      const int r_req = r_nxt >= 0 ? r_nxt : r_cur;
+      const uint32_t k_tile = slot(2 * pair), v_tile = slot(2 * pair + 1);
+      pipes::fused_step(k_tile + lo.k, v_tile + lo.v[0], v_tile + lo.v[1], w.qf, w.o, w.m, w.l, p.c, tile_ptr(kb, r_req),
+                        tile_ptr(vb, r_req), x_kv, slot_wave(2 * pair + 2), slot_wave(2 * pair + 3));
+      if (kProfile) { prof[0] += t1 - t0; prof[1] += clock32() - t1; prof[4] += 1; }
+      r_cur = r_nxt;
+      ++pair;
+    }
+    // The last tile(s), shifted back to end at the last token: their leading rows are not keys of the tile.
+#pragma unroll 1
+    while (r_cur >= 0) {
+      ring_barrier<NI>(0);
+      const int r_nxt = plan();
+      const int r_req = r_nxt >= 0 ? r_nxt : r_cur;
       const uint32_t k_tile = slot(2 * pair), v_tile = slot(2 * pair + 1);
       f32x16 s0, s1;
       bf16x8 pf[4];  // P^T of the tile
-      // the next pair is requested into the other two slots (after the last pair: once more the same, unused)
-      const int r_req = r_nxt >= 0 ? r_nxt : r_cur;
       pipes::rows_x_q_dma(k_tile + lo.k, w.qf, s0, s1, tile_ptr(kb, r_req), tile_ptr(vb, r_req), x_kv,
                           slot_wave(2 * pair + 2), slot_wave(2 * pair + 3));
       exact_tile_softmax<D>(s0, s1, w, p.c, r_cur - tile_row(r_cur), n - tile_row(r_cur), lane, pf);
-      const uint32_t t2 = kProfile ? clock32() : 0u;
       pipes::cols_x_p64(v_tile + lo.v[0], v_tile + lo.v[1], pf, w.o);
-      if (kProfile) { prof[0] += t1 - t0; prof[1] += t2 - t1; prof[2] += clock32() - t2; prof[4] += 1; }
       r_cur = r_nxt;
       ++pair;
     }
