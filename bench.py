@@ -87,6 +87,7 @@ def main():
     ap.add_argument("--workload", default="wan14b-720p")
     ap.add_argument("--noise-amp", type=float, default=NOISE_AMP_DEFAULT)
     ap.add_argument("--group", type=int, default=32)
+    ap.add_argument("--kv-slices", type=int, default=0, help="key-range slices of the attention kernel (0 = the library's choice)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
@@ -108,7 +109,7 @@ def main():
     torch.cuda.set_device(dev)
     w = workloads.WORKLOADS[args.workload]
     q, k, v = workloads.make_workload_qkv(w, device=dev)
-    shape = P.Shape.of(q, block=w.block, group=args.group)
+    shape = P.Shape.of(q, block=w.block, group=args.group, kv_slices=args.kv_slices)
     nb = P.num_blocks(shape)
     k_sel = P.topk_count(nb, w.keep_ratio)
     bh = w.batch * w.heads
@@ -182,7 +183,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "B": w.batch, "H": w.heads, "n": w.n, "d": w.d, "block": w.block,
                    "keep_ratio": w.keep_ratio, "k_sel": k_sel, "n_blocks": nb, "group": args.group,
-                   "noise_amp": args.noise_amp, "seed": w.seed},
+                   "noise_amp": args.noise_amp, "seed": w.seed, "kv_slices": args.kv_slices},
         "stage_ms": {"block_score": stage_ms[0], "route": stage_ms[1], "kv_stats": stage_ms[2], "sparse_attn": attn_ms},
         "computed_tflops": computed_tflops,
         "algorithmic_tflop": {kk: vv / 1e12 for kk, vv in fl.items()},

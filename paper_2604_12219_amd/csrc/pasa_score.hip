@@ -38,47 +38,43 @@ __global__ void __launch_bounds__(256) pool_mean_kernel(ScoreParams p) {
   }
 }
 
-// scores tile of 64x64 per workgroup; operands staged transposed in LDS ([d][row]) so that a thread
-// reads its 4 rows / 4 columns with one 16-byte LDS read per d.
+// scores: one wave per 32x32 tile, fp32 MFMA (32x32x2: A is 32 rows x 2, B is 2 x 32 columns, one float of
+// each per lane).  The contraction order is free as long as both operands agree, so lane (x = lane & 31,
+// h = lane >> 5) keeps d/2 consecutive floats of row i0 + x of the pooled queries and of row j0 + x of the
+// pooled keys, elements [h*d/2, (h+1)*d/2), straight from global memory (the pooled means of a head are a
+// few hundred KB: L2 traffic), and step s multiplies element s of both.  The four waves of a workgroup
+// take four neighbouring column tiles of the same row tile.
+typedef float f32x16 __attribute__((ext_vector_type(16)));
 template <int D>
 __global__ void __launch_bounds__(256) score_gemm_kernel(ScoreParams p) {
-  constexpr int LD = 68;  // padded leading dimension (floats), keeps 16-byte alignment
-  __shared__ __attribute__((aligned(16))) float a_s[D][LD];
-  __shared__ __attribute__((aligned(16))) float b_s[D][LD];
-  const int bh = blockIdx.z, i0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
-  const int tid = threadIdx.x;
-  const float* qa = p.qbar + (int64_t)bh * p.nb * D;
-  const float* kb = p.kbar + (int64_t)bh * p.nb * D;
-  for (int x = tid; x < 64 * D; x += 256) {
-    const int row = x / D, dd = x % D;
-    a_s[dd][row] = (i0 + row < p.nb) ? qa[(int64_t)(i0 + row) * D + dd] : 0.f;
-    b_s[dd][row] = (j0 + row < p.nb) ? kb[(int64_t)(j0 + row) * D + dd] : 0.f;
+  constexpr int HALF = D / 2;
+  const int bh = blockIdx.z, i0 = blockIdx.y * 32, j0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * 32;
+  if (j0 >= p.nb) return;
+  const int lane = threadIdx.x & 63, x = lane & 31, h = lane >> 5;
+  const float* qa = p.qbar + ((int64_t)bh * p.nb + min(i0 + x, p.nb - 1)) * D + h * HALF;  // rows past the end: clamped, never stored
+  const float* kb = p.kbar + ((int64_t)bh * p.nb + min(j0 + x, p.nb - 1)) * D + h * HALF;
+  float4 a[HALF / 4], b[HALF / 4];
+#pragma unroll
+  for (int c = 0; c < HALF / 4; ++c) {
+    a[c] = reinterpret_cast<const float4*>(qa)[c];
+    b[c] = reinterpret_cast<const float4*>(kb)[c];
   }
-  __syncthreads();
-  const int ty = tid / 16, tx = tid % 16;
-  float acc[4][4] = {};
-#pragma unroll 4
-  for (int dd = 0; dd < D; ++dd) {
-    const float4 a = *reinterpret_cast<const float4*>(&a_s[dd][ty * 4]);
-    const float4 b = *reinterpret_cast<const float4*>(&b_s[dd][tx * 4]);
-    const float av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w};
+  f32x16 acc = {0};
 #pragma unroll
-    for (int y = 0; y < 4; ++y)
-#pragma unroll
-      for (int x = 0; x < 4; ++x) acc[y][x] = fmaf(av[y], bv[x], acc[y][x]);
+  for (int c = 0; c < HALF / 4; ++c) {
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[c].x, b[c].x, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[c].y, b[c].y, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[c].z, b[c].z, acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[c].w, b[c].w, acc, 0, 0, 0);
   }
+  // result register 4g + r of lane (x, h) is row 8g + 4h + r, column x of the tile
+  const int j = j0 + x;
+  if (j >= p.nb) return;
+  const float bias = p.key_bias ? p.key_bias[(int64_t)bh * p.nb + j] : 0.f;
 #pragma unroll
-  for (int y = 0; y < 4; ++y) {
-    const int i = i0 + ty * 4 + y;
-    if (i >= p.nb) continue;
-#pragma unroll
-    for (int x = 0; x < 4; ++x) {
-      const int j = j0 + tx * 4 + x;
-      if (j >= p.nb) continue;
-      float s = acc[y][x] * p.scale;
-      if (p.key_bias) s += p.key_bias[(int64_t)bh * p.nb + j];
-      p.scores[((int64_t)bh * p.nb + i) * p.nb + j] = s;
-    }
+  for (int r = 0; r < 16; ++r) {
+    const int i = i0 + 8 * (r >> 2) + 4 * h + (r & 3);
+    if (i < p.nb) p.scores[((int64_t)bh * p.nb + i) * p.nb + j] = fmaf(acc[r], p.scale, bias);
   }
 }
 
@@ -86,8 +82,8 @@ __global__ void __launch_bounds__(256) score_gemm_kernel(ScoreParams p) {
 
 hipError_t pasa_launch_block_score(const ScoreParams& p, hipStream_t stream) {
   const dim3 gp(p.nb, p.bh, 2);
-  const int tiles = (p.nb + 63) / 64;
-  const dim3 gg(tiles, tiles, p.bh);
+  const int tiles = (p.nb + 31) / 32;
+  const dim3 gg((tiles + 3) / 4, tiles, p.bh);
   if (p.d == 128) {
     hipLaunchKernelGGL(pool_mean_kernel<128>, gp, dim3(256), 0, stream, p);
     hipLaunchKernelGGL(score_gemm_kernel<128>, gg, dim3(256), 0, stream, p);

@@ -136,3 +136,14 @@ def test_binding_raises_a_clear_error_when_the_library_is_missing(P, monkeypatch
     monkeypatch.setattr(mod, "_LIB_PATH", "/nonexistent/libpasa_hip.so")
     with pytest.raises(RuntimeError, match="no CPU fallback"):
         mod.load_library()
+
+
+def test_generated_mfma_sequences_are_up_to_date():
+    """pasa_mfma_pipes.hpp is written by gen_mfma_pipes.py; the committed header must be what the generator emits"""
+    import importlib.util
+    csrc = os.path.join(ROOT, "paper_2604_12219_amd", "csrc")
+    spec = importlib.util.spec_from_file_location("gen_mfma_pipes", os.path.join(csrc, "gen_mfma_pipes.py"))
+    gen = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(gen)
+    with open(os.path.join(csrc, "pasa_mfma_pipes.hpp")) as f:
+        assert f.read() == gen.gen()

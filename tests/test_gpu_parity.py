@@ -136,6 +136,10 @@ CASES = [
     ((9, 20, 23), 1, 128, 64, 8, 0.15),     # small groups
     ((9, 20, 23), 1, 128, 64, 1, 0.05),     # per-block first-order term (Eq.13)
     ((9, 20, 23), 1, 64, 128, 32, 0.1),
+    ((1, 5, 7), 1, 128, 64, 32, 1.0),       # n=35: shorter than one tile
+    ((1, 9, 11), 2, 64, 64, 32, 0.5),       # n=99: two blocks, the second one ragged; one block each selected
+    ((2, 16, 16), 1, 128, 64, 32, 0.3),     # n=512: no ragged tile at all
+    ((1, 9, 11), 1, 128, 128, 32, 1.0),     # n=99 with 128-token blocks: a single block, its second tile ragged
 ]
 
 
