@@ -25,8 +25,9 @@
  *     reported as PASA_EHIP (hipGetLastError after the launch; never a device synchronise).
  *   - Outputs must not alias inputs.  Base pointers must be 16-byte aligned and strides multiples of
  *     8 elements (PASA_EALIGN otherwise).
- *   - Results are deterministic: no atomics, fixed reduction order; the same inputs give the same
- *     bits on every call.
+ *   - Results are deterministic: no floating-point atomics, fixed reduction order; the same inputs
+ *     give the same bits on every call (also with key-range slicing, whose work queue only decides
+ *     which workgroup computes an item, not what it computes).
  */
 #ifndef PASA_H_
 #define PASA_H_
@@ -143,7 +144,8 @@ PASA_API int pasa_kv_stats(const void* k, const void* v, const pasa_shape_t* sha
  * attention kernel).  pasa_sparse_attn_fwd_prepared runs the attention kernel alone and requires
  * that `ws` was filled by pasa_kv_stats for the same k, v and shape and not touched since.
  *   idx    int32 [BH, N_B, k_sel], each row strictly ascending, values in [0, N_B) (not checked)
- *   mask   the bitmap pasa_route wrote for the same idx
+ *   mask   the bitmap pasa_route wrote for the same idx.  The kernels walk the bitmap; idx is part of
+ *          the interface for callers and checkers and must describe the same selection.
  *   out    bf16 [B,H,n,d] (shape strides)
  *   lse    fp32 [BH, n] or NULL: log(Den) including the subtracted maximum
  *   ws     scratch of pasa_attn_workspace_bytes(shape) bytes, 256-byte aligned

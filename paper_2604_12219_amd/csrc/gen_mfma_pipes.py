@@ -177,9 +177,9 @@ def max_stream(S):
             f"v_max_f32 {t0}, {t0}, {t1}", f"v_mul_f32 {t0}, %[c], {t0}"]
 
 
-def exp_stream(S, P):
-    """p = exp2(s c - m) in place, the two P^T fragments into v[P:P+7], l += sum.  Three-stage pipeline so
-    that no instruction uses the result of the transcendental issued right before it."""
+def exp_stream(S, P, convert=True):
+    """p = exp2(s c - m) in place, the two P^T fragments into v[P:P+7] (if convert), l += sum.  Three-stage
+    pipeline so that no instruction uses the result of the transcendental issued right before it."""
     s = lambda i: vr(S + i)
     t4 = vr(FS_T + 4)
     out = []
@@ -196,13 +196,17 @@ def exp_stream(S, P):
                 out.append(f"v_add_f32 {t4}, {s(1)}, {s(3)}")
             elif e > 3:
                 out.append(f"v_add_f32 {t4}, {t4}, {s(e)}")
-            if e % 2 == 1:
+            if e % 2 == 1 and convert:
                 out.append(f"v_cvt_pk_bf16_f32 {vr(P + e // 2)}, {s(e - 1)}, {s(e)}")
     out.append(f"v_add_f32 %[l], %[l], {t4}")
     return out
 
 
-def raise_max(n_o, now):
+def convert_stream(S, P):
+    return [f"v_cvt_pk_bf16_f32 {vr(P + j)}, {vr(S + 2 * j)}, {vr(S + 2 * j + 1)}" for j in range(8)]
+
+
+def raise_max(n_o, now, also=()):
     """after max_stream: if the maximum grew for some lane, m <- max(m, T0), T3 = exp2(m_old - m), l *= T3, and
     either the accumulators too (now) or the wave-uniform decision is left in %[flag] for later.
     The conditional part is one item: it must not be split up (nothing else may sit between branch and label)."""
@@ -216,6 +220,7 @@ def raise_max(n_o, now):
             f"v_mov_b32 %[m], {t1}", "s_nop 0", f"v_mul_f32 %[l], %[l], {t3}"]
     if now:
         cond += [f"v_mul_f32 {vr(FS_O + i)}, {vr(FS_O + i)}, {t3}" for i in range(n_o)]
+    cond += [f"v_mul_f32 {r}, {r}, {t3}" for r in also]  # e.g. weights computed against the old maximum, not yet used
     cond.append(f".Lfs_keep{tag}_%=:")
     out.append(tuple(cond))
     return out
@@ -325,6 +330,57 @@ def asm_block(lines, outs, ins, extra_clobbers=()):
     return f"  asm volatile(\n{text}\n      : {', '.join(outs)}\n      : {', '.join(ins)}\n      : {clob});\n"
 
 
+def logits_softmax(D):
+    """The first half of fused_step for loops that must meet a barrier before P V (the V tile lands later):
+    S0, S1 = K Q^T with the softmax of S0 in the shadow of the MFMAs of S1, then the softmax of S1; leaves
+    P0, P1.  No MFMA adds to the accumulators meanwhile, so both halves rescale them at once; the weights of the
+    first half stay fp32 until the second half has settled the maximum."""
+    ns, nt = D // 16, D // 32
+    ni = (64 // (1024 // (2 * D))) // 4
+    n_o = 16 * nt
+    mf = []
+    for half in range(2):
+        for st in range(ns):
+            mf.append(dict(acc=vr(FS_S0 if half == 0 else FS_S1, 16), first=(st == 0), b=f"%[q{st}]", load=("k", st, half)))
+    n = len(mf)
+    after = {}
+    spread(after, ns + 1, n - 1, max_stream(FS_S0) + raise_max(n_o, True) + exp_stream(FS_S0, FS_P0, convert=False))
+    lines = []
+    pipe = LdsPipe(lines, D)
+    pipe.k_addresses()
+    for k in range(pipe.nbuf):
+        pipe.issue(k, mf[k]["load"])
+    dmas = [("k", j) for j in range(ni)] + [("v", j) for j in range(ni)]
+    for k in range(n):
+        pipe.wait_for(k)
+        m = mf[k]
+        lines.append(f"{MFMA} {m['acc']}, {F(k % pipe.nbuf)}, {m['b']}, {'0' if m['first'] else m['acc']}")
+        if dmas:
+            lines.append(f"s_add_u32 m0, %[l{dmas[0][0]}], {hex(dmas[0][1] * 4096)}")
+        if k + pipe.nbuf < n:
+            pipe.issue(k + pipe.nbuf, mf[k + pipe.nbuf]["load"])
+        elif dmas:
+            lines.append("s_nop 0")
+        if dmas:
+            which, jj = dmas.pop(0)
+            lines.append(f"global_load_lds_dwordx4 %[x{jj}], %[{which}b]")
+        lines += after.get(k, [])
+    assert not dmas
+    lines.append(NOP_AFTER)  # the last MFMA of S1 has to deliver before its maximum is taken
+    # the weights of the first half are still fp32: if the second half raises the maximum they follow it
+    for item in max_stream(FS_S1) + raise_max(n_o, True, also=[vr(FS_S0 + i) for i in range(16)]) + \
+            convert_stream(FS_S0, FS_P0) + exp_stream(FS_S1, FS_P1):
+        lines += list(item) if isinstance(item, tuple) else [item]
+    # raise_max(.., True) is used twice in this sequence: make its labels distinct
+    seen, out = 0, []
+    for l in lines:
+        if "Lfs_keepa" in l:
+            l = l.replace("Lfs_keepa", "Lfs_keepa" if seen < 2 else "Lfs_keepc")
+            seen += 1
+        out.append(l)
+    return out
+
+
 # Operands that are MFMA results or inputs of several sequences are bound to the same registers everywhere,
 # which leaves the register allocator nothing to get wrong: accumulators O v[0:63], logits v[168:199],
 # P^T fragments v[200:215].
@@ -403,6 +459,22 @@ def gen():
               ['[kb] "s"(kb)', '[vb] "s"(vb)', '[lk] "s"(lk)', '[lv] "s"(lv)'] + [f'[x{j}] "v"(x[{j}])' for j in range(ni)]
         text = "\n".join(f'      "{l}\\n\\t"' for l in fused_step(D))
         clob = ", ".join([f'"v{r}"' for r in range(FUSED_CLOBBER_LO, 256)] + ['"memory"', '"scc"', '"vcc"', '"m0"'])
+        out.append(f"  asm volatile(\n{text}\n      : {', '.join(outs)}\n      : {', '.join(ins)}\n      : {clob});\n}}\n\n")
+    for D in (128, 64):
+        ns, nt = D // 16, D // 32
+        ni = (64 // (1024 // (2 * D))) // 4
+        out.append(f"// Logits and online softmax of one whole 64-key tile (all keys valid); leaves the P^T fragments p.  Two more\n"
+                   f"// tiles are requested meanwhile (see rows_x_q_dma).  Arguments as in fused_step.\n"
+                   f"PASA_DEVICE void logits_softmax(uint32_t ak, const bf16x8 (&q)[{ns}], f32x16 (&o)[{nt}], float& m, float& l, float c,\n"
+                   f"                               bf16x8 (&p)[4], const void* kb, const void* vb, const uint32_t (&x)[{ni}],\n"
+                   f"                               uint32_t lk, uint32_t lv) {{\n")
+        outs = o_ops(nt) + ['[m] "+v"(m)', '[l] "+v"(l)'] + \
+               [f'[p{k}] "=&{{v[{200 + 4 * k}:{200 + 4 * k + 3}]}}"(p[{k}])' for k in range(4)]
+        ins = ['[ak] "v"(ak)', '[c] "s"(c)'] + q_inputs(D) + \
+              ['[kb] "s"(kb)', '[vb] "s"(vb)', '[lk] "s"(lk)', '[lv] "s"(lv)'] + [f'[x{j}] "v"(x[{j}])' for j in range(ni)]
+        text = "\n".join(f'      "{l}\\n\\t"' for l in logits_softmax(D))
+        clob = ", ".join([f'"v{r}"' for r in range(168, 200)] + [f'"v{r}"' for r in range(216, 256)] +
+                         ['"memory"', '"scc"', '"vcc"', '"m0"'])
         out.append(f"  asm volatile(\n{text}\n      : {', '.join(outs)}\n      : {', '.join(ins)}\n      : {clob});\n}}\n\n")
     out.append("}  // namespace pipes\n")
     return "".join(out)

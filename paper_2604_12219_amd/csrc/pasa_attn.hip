@@ -480,8 +480,29 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
       ring_barrier<NI>(0);  // every wave is done with the ring
       request(kb, (a_blk != kNoBlock ? a_blk : b_blk) * 64, 0);
       request(kb, (b_blk != kNoBlock ? b_blk : a_blk) * 64, 2);
+      // Steps in which both query blocks have a block of their own whose 64 rows are all keys: logits and
+      // softmax as one instruction stream.  (Blocks come in ascending order, so the ragged last block and the
+      // steps in which one list has run out can only be the last ones.)
+      auto whole = [&](int blk) -> bool { return blk != kNoBlock && blk * 64 + 64 <= n; };
+      const uint32_t k_mine = slot(second ? 2 : 0), v_mine = slot(second ? 3 : 1);
 #pragma unroll 1
-      do {
+      while (whole(a_blk) && whole(b_blk)) {
+        ring_barrier<NI>(0);  // the K tiles have landed; the V slots are free
+        const int a_nxt = only_a.next(), b_nxt = only_b.next();
+        const int a_rq2 = a_nxt != kNoBlock ? a_nxt : b_nxt != kNoBlock ? b_nxt : a_blk;
+        const int b_rq2 = b_nxt != kNoBlock ? b_nxt : a_rq2;
+        bf16x8 pf[4];
+        pipes::logits_softmax(k_mine + lo.k, w.qf, w.o, w.m, w.l, p.c, pf, tile_ptr(vb, a_blk * 64), tile_ptr(vb, b_blk * 64),
+                              x_kv, slot_wave(1), slot_wave(3));
+        ring_barrier<NI>(0);  // the V tiles have landed; the K slots are free
+        pipes::cols_x_p64_dma(v_mine + lo.v[0], v_mine + lo.v[1], pf, w.o, tile_ptr(kb, a_rq2 * 64), tile_ptr(kb, b_rq2 * 64),
+                              x_kv, slot_wave(0), slot_wave(2));
+        a_blk = a_nxt;
+        b_blk = b_nxt;
+        if (kProfile) prof[5] += 1;
+      }
+#pragma unroll 1
+      while (a_blk != kNoBlock || b_blk != kNoBlock) {
         ring_barrier<NI>(0);  // the K tiles have landed; the V slots are free
         // With key-range slicing one of the two query blocks can run out of blocks before the other.
         // Its waves then go through the motions on the other block's tiles with an empty key window
@@ -508,7 +529,7 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
         a_blk = a_nxt;
         b_blk = b_nxt;
         if (kProfile) prof[5] += 1;
-      } while (a_blk != kNoBlock || b_blk != kNoBlock);
+      }
     }
     if (kProfile) prof[3] += clock32() - t0;
   }
@@ -607,6 +628,9 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
   }
 
   // ---- epilogue ----
+  // The last steps of the tile loops repeat a request that nobody consumes: let those loads land
+  // before this workgroup's LDS can be handed to another one.
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   const float l_tot = half_swap_sum(w.l);
   if (q_row < n) {
     if constexpr (SLICED) {  // leave the partial result of this slice to the merge kernel
