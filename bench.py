@@ -88,6 +88,8 @@ def main():
     ap.add_argument("--noise-amp", type=float, default=NOISE_AMP_DEFAULT)
     ap.add_argument("--group", type=int, default=32)
     ap.add_argument("--kv-slices", type=int, default=0, help="key-range slices of the attention kernel (0 = the library's choice)")
+    ap.add_argument("--with-prior", action="store_true",
+                    help="route on the full logit of Eq.8: statistics first, then the covariance prior as key bias (not the default path)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
@@ -123,14 +125,26 @@ def main():
     n_ev = args.steps
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(n_ev)]
 
+    beta = torch.empty((bh, nb), dtype=torch.float32, device=dev) if args.with_prior else None
+
     def step(i, events=None):
-        if events: events[0].record()
-        P.block_score(q, k, shape, scores=scores, ws=ws_score)
-        if events: events[1].record()
-        P.route(scores, k_sel, w.seed + i, args.noise_amp, idx=idx, mask=mask)
-        if events: events[2].record()
-        P.kv_stats(k, v, shape, ws=ws_attn)
-        if events: events[3].record()
+        if args.with_prior:  # statistics first: the prior needs them; its time is booked under block_score
+            P.kv_stats(k, v, shape, ws=ws_attn)
+            if events: events[0].record()
+            P.key_prior(k, v, shape, ws_attn, beta=beta)
+            P.block_score(q, k, shape, key_bias=beta, scores=scores, ws=ws_score)
+            if events: events[1].record()
+            P.route(scores, k_sel, w.seed + i, args.noise_amp, idx=idx, mask=mask)
+            if events: events[2].record()
+            if events: events[3].record()
+        else:
+            if events: events[0].record()
+            P.block_score(q, k, shape, scores=scores, ws=ws_score)
+            if events: events[1].record()
+            P.route(scores, k_sel, w.seed + i, args.noise_amp, idx=idx, mask=mask)
+            if events: events[2].record()
+            P.kv_stats(k, v, shape, ws=ws_attn)
+            if events: events[3].record()
         P.sparse_attn_fwd(q, k, v, shape, idx, mask, out=out, ws=ws_attn, prepared=True)
         if events: events[4].record()
 
@@ -183,7 +197,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "B": w.batch, "H": w.heads, "n": w.n, "d": w.d, "block": w.block,
                    "keep_ratio": w.keep_ratio, "k_sel": k_sel, "n_blocks": nb, "group": args.group,
-                   "noise_amp": args.noise_amp, "seed": w.seed, "kv_slices": args.kv_slices},
+                   "noise_amp": args.noise_amp, "seed": w.seed, "kv_slices": args.kv_slices, "covariance_prior": args.with_prior},
         "stage_ms": {"block_score": stage_ms[0], "route": stage_ms[1], "kv_stats": stage_ms[2], "sparse_attn": attn_ms},
         "computed_tflops": computed_tflops,
         "algorithmic_tflop": {kk: vv / 1e12 for kk, vv in fl.items()},

@@ -6,6 +6,7 @@
  * can see every intermediate:
  *
  *   pasa_block_score      block-pooled Q/K routing logits             (Eq.8 without its row softmax)
+ *   pasa_key_prior        optional covariance prior of the routing logits (Eq.8, second term)
  *   pasa_route            seeded stochastic top-k block selection     (Eq.2 + Sec. "Stochastic Routing")
  *   pasa_sparse_attn_fwd  exact attention over the selected blocks + grouped Taylor approximation
  *                         of the unselected ones under one normaliser (Eq.7, Eq.4, Eq.5, Eq.12, Eq.14)
@@ -131,6 +132,19 @@ PASA_API int pasa_route(const float* scores, int32_t BH, int32_t n_blocks, int32
  */
 PASA_API int pasa_kv_stats(const void* k, const void* v, const pasa_shape_t* shape, void* ws, size_t ws_bytes,
                            void* stream);
+
+/*
+ * Covariance-aware routing prior (Eq.8's second term): for every key block
+ *   beta[bh, j] = log( || H_j - Hg_{g(j)} ||_F + eps ),
+ * H_j the first-order statistic of the block (Eq.5), Hg_{g(j)} the mean over the blocks of its group
+ * (Eq.12; Eq.6 when the group is the whole sequence), || ||_F the Frobenius norm (the norm of the paper's
+ * error analysis), both without the logit scale.  Feed the result to pasa_block_score as key_bias to
+ * obtain the full routing logit of Eq.8.  Requires that `ws` was filled by pasa_kv_stats for the same
+ * k, v and shape (it reads the group sums left there) and shape->group > 0 (PASA_EUNSUPPORTED otherwise).
+ *   k, v   bf16 [B,H,n,d] (shape strides);  eps >= 0;  beta fp32 [B*H, N_B] contiguous (out)
+ */
+PASA_API int pasa_key_prior(const void* k, const void* v, const pasa_shape_t* shape, float eps, float* beta,
+                            void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Stages 3 and 4 -- piecewise attention (Eq.7 with the grouped first-order term of Eq.14).

@@ -153,6 +153,24 @@ def kv_stats(k, v, block: int, group: int, want_hj: bool = False):
     return dict(kbar=kbar, vs=vs, hj=hj, hg=hg)
 
 
+def key_prior(k, v, block: int, group: int, eps: float = 1e-6):
+    """Covariance-aware routing prior, the second term of Eq.8, for every key block:
+    beta[bh, j] = log(||H_j - Hg_{g(j)}||_F + eps), H_j as in Eq.5, Hg the mean of H_j over the group of
+    `group` consecutive blocks that contains j (Eq.12; group >= N_B: the global mean of Eq.6), Frobenius
+    norm, no logit scale.  Written out from oracle_kv_stats' H_j and Hg."""
+    assert group > 0
+    st = kv_stats(k, v, block, group, want_hj=True)
+    hj, hg = st["hj"], st["hg"]
+    BH, NB = hj.shape[:2]
+    g_eff = min(group, NB)
+    beta = np.empty((BH, NB), np.float64)
+    for bh in range(BH):
+        for j in range(NB):
+            diff = hj[bh, j] - hg[bh, j // g_eff]
+            beta[bh, j] = np.log(np.sqrt((diff * diff).sum()) + eps)
+    return beta
+
+
 def dense_attention(q, k, v, scale: float | None = None, q_rows=None, return_lse: bool = False):
     q, k, v = _bhnd(q), _bhnd(k), _bhnd(v)
     BH, n, d = q.shape

@@ -12,6 +12,7 @@ from .pasa import (  # noqa: F401
     attn_workspace_bytes,
     block_score,
     forward,
+    key_prior,
     kv_stats,
     lib_path,
     load_library,

@@ -209,6 +209,28 @@ int pasa_kv_stats(const void* k, const void* v, const pasa_shape_t* shape, void*
   return pasa_launch_kv_stats(t, static_cast<hipStream_t>(stream)) == hipSuccess ? PASA_OK : PASA_EHIP;
 }
 
+int pasa_key_prior(const void* k, const void* v, const pasa_shape_t* shape, float eps, float* beta, void* ws,
+                   size_t ws_bytes, void* stream) {
+  pasa_shape_t s;
+  const int rc = check_attn_args(shape, true, ws, ws_bytes, &s);
+  if (rc != PASA_OK) return rc;
+  if (!k || !v || !beta || !(eps >= 0.f)) return PASA_EINVAL;
+  if (!aligned16(k) || !aligned16(v)) return PASA_EALIGN;
+  if (s.group == 0) return PASA_EUNSUPPORTED;
+  const int nb = num_blocks(&s);
+  const AttnWorkspace w = carve_attn(&s);
+  char* base = static_cast<char*>(ws);
+  StatsParams t{};
+  t.k = static_cast<const uint16_t*>(k); t.v = static_cast<const uint16_t*>(v);
+  t.stride_b = s.stride_b; t.stride_h = s.stride_h; t.stride_n = s.stride_n;
+  t.bh = s.B * s.H; t.H = s.H; t.n = s.n; t.nb = nb; t.block = s.block; t.tail = s.n - (nb - 1) * s.block; t.d = s.d;
+  t.group = s.group >= nb ? nb : s.group; t.n_groups = w.n_groups; t.unit = w.unit; t.n_units = w.n_units;
+  t.scale = effective_scale(&s);
+  t.n_chunks = w.n_chunks;
+  t.partial = reinterpret_cast<float*>(base + w.partial);
+  return pasa_launch_key_prior(t, eps, beta, static_cast<hipStream_t>(stream)) == hipSuccess ? PASA_OK : PASA_EHIP;
+}
+
 static int attn_common(const void* q, const void* k, const void* v, const pasa_shape_t* shape, const int32_t* idx,
                        const uint32_t* mask, int32_t k_sel, void* out, float* lse, void* ws, size_t ws_bytes,
                        void* stream, bool sparse, bool with_stats) {

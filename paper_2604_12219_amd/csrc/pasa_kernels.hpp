@@ -51,6 +51,8 @@ struct StatsParams {
   uint16_t* hg;      // out bf16 [BH][n_groups][d][d] (see AttnParams::hg)
 };
 hipError_t pasa_launch_kv_stats(const StatsParams& p, hipStream_t stream);
+// beta [BH][nb] fp32 = log(||H_j - Hg_{g(j)}||_F + eps); needs p.partial as pasa_launch_kv_stats left it
+hipError_t pasa_launch_key_prior(const StatsParams& p, float eps, float* beta, hipStream_t stream);
 
 struct ScoreParams {
   const uint16_t* q;

@@ -147,6 +147,130 @@ __global__ void __launch_bounds__(256) hg_finish_kernel(StatsParams p) {
   }
 }
 
+// Covariance-aware routing prior (Eq.8): beta_j = log(|| H_j - Hg_{g(j)} ||_F + eps) for every key block.
+// Same sweep as kv_stats_kernel -- a workgroup owns a unit of consecutive blocks of one group, K^T V on the
+// matrix cores, rank-one correction in fp32 -- but H_j is formed per block and compared, element by element
+// in fp32, with the group mean, which the workgroup first sums up from the unit sums that kv_stats_kernel
+// left (`partial`).  Nothing but beta is written.
+template <int D>
+__global__ void __launch_bounds__(256) key_prior_kernel(StatsParams p, float eps, float* beta) {
+  constexpr int T = 256;
+  constexpr int TI = D / 64;
+  constexpr int TILE_BYTES = 64 * 2 * D;
+  __shared__ __attribute__((aligned(16))) char smem[2 * TILE_BYTES];
+  __shared__ float kmean_s[D], vsum_s[D], red_s[4];
+  char* const k_lds = smem;
+  char* const v_lds = smem + TILE_BYTES;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5;
+  const int u = blockIdx.x, bh = blockIdx.y;
+  const int64_t head_off = (int64_t)(bh / p.H) * p.stride_b + (int64_t)(bh % p.H) * p.stride_h;
+  const uint16_t* const kb = p.k + head_off;
+  const uint16_t* const vb = p.v + head_off;
+  const int j_lo = u * p.unit, j_hi = min(j_lo + p.unit, p.nb);
+  const int tiles_per_block = p.block / 64;
+  const int tin0 = (wave >> 1) * TI, tout0 = (wave & 1) * TI;
+
+  // the group this unit belongs to, and its mean: sum of the group's unit sums / blocks in the group
+  const int g = j_lo / p.group;
+  int upg = 1;  // units per group
+  if (p.group > 32) upg = (p.group >= p.nb) ? p.n_units : p.group / 32;
+  const int u_lo = g * upg, u_hi = min(u_lo + upg, p.n_units);
+  const float inv_blocks = 1.0f / (float)(min((g + 1) * p.group, p.nb) - g * p.group);
+  f32x16 mean[TI][TI];
+#pragma unroll
+  for (int a = 0; a < TI; ++a)
+#pragma unroll
+    for (int b = 0; b < TI; ++b) {
+      mean[a][b] = f32x16{0};
+      for (int uu = u_lo; uu < u_hi; ++uu) {
+        const float* part = p.partial + ((int64_t)bh * p.n_units + uu) * D * D;
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          mean[a][b][r] += part[(32 * (tin0 + a) + mfma_row(r, h)) * D + 32 * (tout0 + b) + (lane & 31)];
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mean[a][b][r] *= inv_blocks;
+    }
+
+  f32x16 acc[TI][TI];
+#pragma unroll
+  for (int a = 0; a < TI; ++a)
+#pragma unroll
+    for (int b = 0; b < TI; ++b) acc[a][b] = f32x16{0};
+
+  const bool is_k_col = tid < D, is_v_col = (tid >= D) && (tid < 2 * D);
+  const int col = is_k_col ? tid : tid - D;
+  float colsum = 0.f;
+
+  TileStage<D, T> sk, sv;
+  const int n_tiles = (j_hi - j_lo) * tiles_per_block;
+  auto tile_row0 = [&](int t) { return (j_lo + t / tiles_per_block) * p.block + (t % tiles_per_block) * 64; };
+  sk.load(kb, p.stride_n, tile_row0(0), 64, p.n, tid);
+  sv.load(vb, p.stride_n, tile_row0(0), 64, p.n, tid);
+
+  for (int t = 0; t < n_tiles; ++t) {
+    sk.store(k_lds, 64, tid);
+    sv.store(v_lds, 64, tid);
+    __syncthreads();
+    if (t + 1 < n_tiles) {
+      sk.load(kb, p.stride_n, tile_row0(t + 1), 64, p.n, tid);
+      sv.load(vb, p.stride_n, tile_row0(t + 1), 64, p.n, tid);
+    }
+    if (is_k_col || is_v_col) {
+      const char* src = is_k_col ? k_lds : v_lds;
+#pragma unroll 8
+      for (int r = 0; r < 64; ++r) {
+        const __bf16 x = *reinterpret_cast<const __bf16*>(src + lds_chunk_off<D>(r, col >> 3) + (col & 7) * 2);
+        colsum += (float)x;
+      }
+    }
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      bf16x8 af[TI], bf[TI];
+#pragma unroll
+      for (int a = 0; a < TI; ++a) af[a] = col_frag<D>(k_lds, 16 * ks, 32 * (tin0 + a), lane);
+#pragma unroll
+      for (int b = 0; b < TI; ++b) bf[b] = col_frag<D>(v_lds, 16 * ks, 32 * (tout0 + b), lane);
+#pragma unroll
+      for (int a = 0; a < TI; ++a)
+#pragma unroll
+        for (int b = 0; b < TI; ++b) acc[a][b] = mfma32(af[a], bf[b], acc[a][b]);
+    }
+    const bool block_done = (t % tiles_per_block) == tiles_per_block - 1;
+    const int j = j_lo + t / tiles_per_block;
+    if (block_done) {
+      const int len = (j == p.nb - 1) ? p.tail : p.block;
+      if (is_k_col) kmean_s[col] = colsum / (float)len;
+      else if (is_v_col) vsum_s[col] = colsum;
+      colsum = 0.f;
+    }
+    __syncthreads();  // tiles consumed; block statistics visible
+    if (block_done) {
+      float ss = 0.f;
+#pragma unroll
+      for (int a = 0; a < TI; ++a)
+#pragma unroll
+        for (int b = 0; b < TI; ++b) {
+          const float vcol = vsum_s[32 * (tout0 + b) + (lane & 31)];
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const float hj = acc[a][b][r] - kmean_s[32 * (tin0 + a) + mfma_row(r, h)] * vcol;
+            const float dlt = hj - mean[a][b][r];
+            ss = fmaf(dlt, dlt, ss);
+          }
+          acc[a][b] = f32x16{0};
+        }
+#pragma unroll
+      for (int sh = 32; sh >= 1; sh >>= 1) ss += __shfl_xor(ss, sh);
+      if (lane == 0) red_s[wave] = ss;
+      __syncthreads();
+      if (tid == 0) beta[(int64_t)bh * p.nb + j] = logf(sqrtf(red_s[0] + red_s[1] + red_s[2] + red_s[3]) + eps);
+      // red_s, kmean_s and vsum_s are next written after the barrier at the top of the next tile
+    }
+  }
+}
+
 }  // namespace
 
 hipError_t pasa_launch_kv_stats(const StatsParams& p, hipStream_t stream) {
@@ -158,5 +282,12 @@ hipError_t pasa_launch_kv_stats(const StatsParams& p, hipStream_t stream) {
     hipLaunchKernelGGL(kv_stats_kernel<64>, g1, dim3(256), 0, stream, p);
     hipLaunchKernelGGL(hg_finish_kernel<64>, g2, dim3(256), 0, stream, p);
   }
+  return hipGetLastError();
+}
+
+hipError_t pasa_launch_key_prior(const StatsParams& p, float eps, float* beta, hipStream_t stream) {
+  dim3 g1(p.n_units, p.bh);
+  if (p.d == 128) hipLaunchKernelGGL(key_prior_kernel<128>, g1, dim3(256), 0, stream, p, eps, beta);
+  else hipLaunchKernelGGL(key_prior_kernel<64>, g1, dim3(256), 0, stream, p, eps, beta);
   return hipGetLastError();
 }

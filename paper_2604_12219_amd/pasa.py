@@ -16,7 +16,7 @@ _LIB_PATH = os.path.join(_HERE, "libpasa_hip.so")
 _lib = None
 
 EXPORTS = ("pasa_strerror", "pasa_topk_count", "pasa_num_blocks", "pasa_mask_words", "pasa_score_workspace_bytes",
-           "pasa_attn_workspace_bytes", "pasa_block_score", "pasa_route", "pasa_kv_stats", "pasa_sparse_attn_fwd",
+           "pasa_attn_workspace_bytes", "pasa_block_score", "pasa_route", "pasa_kv_stats", "pasa_key_prior", "pasa_sparse_attn_fwd",
            "pasa_sparse_attn_fwd_prepared", "pasa_attn_dense_ref")
 
 
@@ -96,6 +96,8 @@ def load_library() -> ctypes.CDLL:
         L.pasa_sparse_attn_fwd_prepared.argtypes = L.pasa_sparse_attn_fwd.argtypes
         L.pasa_kv_stats.restype = ctypes.c_int
         L.pasa_kv_stats.argtypes = [vp, vp, sp, vp, ctypes.c_size_t, vp]
+        L.pasa_key_prior.restype = ctypes.c_int
+        L.pasa_key_prior.argtypes = [vp, vp, sp, ctypes.c_float, vp, vp, ctypes.c_size_t, vp]
         L.pasa_attn_dense_ref.restype = ctypes.c_int
         L.pasa_attn_dense_ref.argtypes = [vp, vp, vp, sp, vp, vp, vp, ctypes.c_size_t, vp]
         _lib = L
@@ -178,6 +180,16 @@ def kv_stats(k, v, shape: Shape, ws=None):
     ws = _workspace(attn_workspace_bytes(shape), k.device, ws)
     _check(L.pasa_kv_stats(_ptr(k), _ptr(v), ctypes.byref(shape.c()), _ptr(ws), ws.numel(), _stream()), "pasa_kv_stats")
     return ws
+
+
+def key_prior(k, v, shape: Shape, ws, eps: float = 1e-6, beta=None):
+    """covariance-aware routing prior beta [B*H, N_B]; ``ws`` must hold kv_stats() of the same k, v, shape"""
+    L = load_library()
+    if beta is None:
+        beta = torch.empty((shape.B * shape.H, num_blocks(shape)), dtype=torch.float32, device=k.device)
+    _check(L.pasa_key_prior(_ptr(k), _ptr(v), ctypes.byref(shape.c()), eps, _ptr(beta), _ptr(ws), ws.numel(), _stream()),
+           "pasa_key_prior")
+    return beta
 
 
 def sparse_attn_fwd(q, k, v, shape: Shape, idx, mask, out=None, lse=None, ws=None, want_lse: bool = False,

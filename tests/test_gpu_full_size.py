@@ -98,3 +98,23 @@ def test_budget_schedule_runs_with_runtime_k(P):
                                     group=32, q_blocks=blocks)
         rows = np.concatenate([np.arange(j * w.block, min((j + 1) * w.block, w.n)) for j in blocks])
         assert_close(to_f64(out[:, :1]), res, rows=rows, what=f"budget step {step}")
+
+
+def test_full_size_key_prior_of_one_head_against_oracle(P):
+    """covariance-aware routing prior at the Wan-14B 720p shape: every block of one head, and the timing printed"""
+    w = workloads.WORKLOADS["wan14b-720p"]
+    q, k, v = workloads.make_workload_qkv(w, device="cuda")
+    shape = P.Shape.of(q, block=w.block, group=32)
+    ws = P.kv_stats(k, v, shape)
+    beta = P.key_prior(k, v, shape, ws)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(3):
+        P.key_prior(k, v, shape, ws, beta=beta)
+    e1.record()
+    torch.cuda.synchronize()
+    print(f"pasa_key_prior at wan14b-720p: {e0.elapsed_time(e1) / 3:.3f} ms")
+    head = 23
+    ref = oracle.key_prior(to_f64(k[:, head:head + 1]), to_f64(v[:, head:head + 1]), w.block, 32)
+    np.testing.assert_allclose(beta.cpu().numpy()[head], ref[0], atol=2e-3, rtol=0)

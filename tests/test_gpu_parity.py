@@ -71,6 +71,28 @@ def test_block_scores_match_oracle(P, grid, d, block):
     np.testing.assert_allclose(s1.cpu().numpy(), ref + bias.cpu().numpy()[:, None, :], atol=tol, rtol=0)
 
 
+@pytest.mark.parametrize("grid,d,block,group", [((4, 16, 16), 64, 64, 32), ((5, 21, 13), 128, 64, 8),
+                                                ((9, 20, 23), 128, 64, 32), ((9, 20, 23), 128, 64, 64),
+                                                ((9, 20, 23), 128, 64, 1000), ((9, 20, 23), 128, 128, 32),
+                                                ((9, 20, 23), 64, 64, 1)])
+def test_key_prior_matches_oracle_and_feeds_the_scores(P, grid, d, block, group):
+    """covariance-aware routing prior (Eq.8): beta against the oracle, then scores with it as key bias"""
+    q, k, v = _inputs(grid, 2, d, seed=5)
+    shape = P.Shape.of(q, block=block, group=group)
+    ws = P.kv_stats(k, v, shape)
+    beta = P.key_prior(k, v, shape, ws, eps=1e-6)
+    torch.cuda.synchronize()
+    ref = oracle.key_prior(to_f64(k), to_f64(v), block, group, eps=1e-6)
+    if group == 1:  # every block is its own group: the norm is rounding noise, only "tiny" can be compared
+        assert np.all(beta.cpu().numpy() < np.log(1e-2)) and np.all(ref < np.log(1e-5))
+    else:
+        np.testing.assert_allclose(beta.cpu().numpy(), ref, atol=2e-3, rtol=0)
+    s = P.block_score(q, k, shape, key_bias=beta)
+    torch.cuda.synchronize()
+    want = oracle.block_scores(to_f64(q), to_f64(k), block) + beta.cpu().numpy().astype(np.float64)[:, None, :]
+    np.testing.assert_allclose(s.cpu().numpy(), want, atol=1e-3 * np.abs(want).max(), rtol=0)
+
+
 # ------------------------------------------------------------------------------------------------
 # stage 2: routing is bit-exact against the oracle fed the GPU's scores
 # ------------------------------------------------------------------------------------------------

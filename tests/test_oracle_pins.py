@@ -412,3 +412,60 @@ def test_huge_amplitude_selects_every_block_equally_often():
         counts += np.bincount(idx.ravel(), minlength=32)
     freq = counts / (200 * 32)
     np.testing.assert_allclose(freq, 8 / 32, atol=0.03)
+
+
+# ------------------------------------------------------------------------------------------------
+# covariance-aware routing prior (Eq.8, second term)
+# ------------------------------------------------------------------------------------------------
+def _brute_force_prior(K, V, b, G, eps):
+    """Eq.5, Eq.12 and the norm written with Python loops over tokens and matrix elements (tiny inputs only)"""
+    n, d = len(K), len(K[0])
+    NB = -(-n // b)
+    H = []
+    for j in range(NB):
+        rows = range(j * b, min((j + 1) * b, n))
+        kbar = [sum(K[r][c] for r in rows) / len(rows) for c in range(d)]
+        H.append([[sum((K[r][a] - kbar[a]) * V[r][c] for r in rows) for c in range(d)] for a in range(d)])
+    G = min(G, NB)
+    out = []
+    for j in range(NB):
+        members = range((j // G) * G, min((j // G + 1) * G, NB))
+        ss = 0.0
+        for a in range(d):
+            for c in range(d):
+                mean = sum(H[m][a][c] for m in members) / len(members)
+                ss += (H[j][a][c] - mean) ** 2
+        out.append(math.log(math.sqrt(ss) + eps))
+    return np.array(out)
+
+
+@pytest.mark.parametrize("G", [1, 2, 3, 100])
+def test_key_prior_against_brute_force(G):
+    g = rng(31)
+    n, d, b = 23, 4, 4  # 6 blocks, the last one of 3 tokens; G=3: two full groups; G=2: three; G=100: one
+    K, V = g.standard_normal((n, d)), g.standard_normal((n, d))
+    got = oracle.key_prior(K[None], V[None], b, G, eps=1e-6)[0]
+    np.testing.assert_allclose(got, _brute_force_prior(K.tolist(), V.tolist(), b, G, 1e-6), rtol=1e-10, atol=1e-10)
+
+
+def test_key_prior_special_cases():
+    g = rng(32)
+    n, d, b = 64, 8, 8
+    K, V = g.standard_normal((n, d)), g.standard_normal((n, d))
+    # a group of one block is its own mean: the norm vanishes and only eps is left
+    np.testing.assert_allclose(oracle.key_prior(K[None], V[None], b, 1, eps=1e-3), math.log(1e-3), atol=1e-9)
+    # identical blocks inside a group: same
+    Kr, Vr = np.tile(K[:b], (8, 1)), np.tile(V[:b], (8, 1))
+    np.testing.assert_allclose(oracle.key_prior(Kr[None], Vr[None], b, 4, eps=1e-3), math.log(1e-3), atol=1e-6)
+    # H is linear in V and invariant to a constant shift of K: beta(K + c, s V) = beta(K, V) + log s  (eps = 0)
+    b0 = oracle.key_prior(K[None], V[None], b, 4, eps=0.0)
+    b1 = oracle.key_prior((K + 3.0)[None], (2.5 * V)[None], b, 4, eps=0.0)
+    np.testing.assert_allclose(b1, b0 + math.log(2.5), atol=1e-9)
+    # one block differs from seven identical ones: closed form from H of the odd block
+    Ko, Vo = Kr.copy(), Vr.copy()
+    Vo[:b] = g.standard_normal((b, d))
+    st = oracle.kv_stats(Ko[None], Vo[None], b, 8, want_hj=True)
+    delta = st["hj"][0, 0] - st["hj"][0, 1]
+    fro = np.linalg.norm(delta)
+    want = np.array([math.log(fro * 7 / 8)] + [math.log(fro / 8)] * 7)
+    np.testing.assert_allclose(oracle.key_prior(Ko[None], Vo[None], b, 8, eps=0.0)[0], want, atol=1e-9)
