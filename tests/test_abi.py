@@ -147,3 +147,8 @@ def test_generated_mfma_sequences_are_up_to_date():
     spec.loader.exec_module(gen)
     with open(os.path.join(csrc, "pasa_mfma_pipes.hpp")) as f:
         assert f.read() == gen.gen()
+
+
+def test_sweeps_module_imports_without_a_gpu():
+    import paper_2604_12219_amd.sweeps as sweeps
+    assert callable(sweeps.main) and callable(sweeps.sweep_groups) and callable(sweeps.selection_histogram)
