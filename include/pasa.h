@@ -178,6 +178,30 @@ PASA_API int pasa_sparse_attn_fwd_prepared(const void* q, const void* k, const v
 PASA_API int pasa_attn_dense_ref(const void* q, const void* k, const void* v, const pasa_shape_t* shape,
                         void* out, float* lse, void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * Curvature-aware dynamic budget (Sec. "Curvature-Aware Dynamic Budgeting").
+ *
+ * pasa_l1_distance: the calibration signal -- mean absolute difference of two tensors of n elements (the
+ * velocity fields of two consecutive denoising steps), out[0] = sum_i |a_i - b_i| / n.  a, b: DEVICE, 16-byte
+ * aligned, dtype PASA_DTYPE_BF16 or PASA_DTYPE_F32; out: DEVICE fp32 scalar; ws: DEVICE scratch of
+ * pasa_l1_workspace_bytes() bytes.  Two kernels on `stream`, fixed summation order (deterministic).
+ *
+ * pasa_budget_schedule: host-only, Eq.9-11.  l1 [n_prompts, n_steps] (host): entry (p, t) is the signal of
+ * calibration prompt p at step t (distance between the velocity fields of steps t-1 and t); rho in (0, 1] the
+ * baseline density; the first floor(dense_fraction * n_steps + 0.5) steps keep full attention (the paper: 20 %)
+ * and get rho_t = 1.  On the other steps  l_t = mean over prompts,  lbar = mean of l_t over those steps (Eq.9),
+ * alpha_t = l_t / lbar (Eq.10),  rho_t = min(1, rho * alpha_t) (Eq.11; the cap at 1 is this library's: a density
+ * cannot exceed "every block").  rho_t [n_steps] (host, out) feeds pasa_topk_count step by step.  Without the cap
+ * the rho_t of the sparse steps sum to rho times their number, the paper's "same total budget".
+ * PASA_EINVAL for negative or non-finite signals or an all-zero signal.
+ */
+enum { PASA_DTYPE_BF16 = 0, PASA_DTYPE_F32 = 1 };
+PASA_API size_t pasa_l1_workspace_bytes(void);
+PASA_API int pasa_l1_distance(const void* a, const void* b, int64_t n, int32_t dtype, float* out, void* ws,
+                              size_t ws_bytes, void* stream);
+PASA_API int pasa_budget_schedule(const double* l1, int32_t n_prompts, int32_t n_steps, double rho,
+                                  double dense_fraction, double* rho_t);
+
 #ifdef __cplusplus
 }
 #endif

@@ -11,6 +11,7 @@ only marshals arguments.
 from __future__ import annotations
 
 import ctypes
+import math
 import os
 import subprocess
 
@@ -169,6 +170,29 @@ def key_prior(k, v, block: int, group: int, eps: float = 1e-6):
             diff = hj[bh, j] - hg[bh, j // g_eff]
             beta[bh, j] = np.log(np.sqrt((diff * diff).sum()) + eps)
     return beta
+
+
+def l1_distance(a, b) -> float:
+    """mean absolute difference of two arrays (the calibration signal of Sec. "Curvature-Aware Dynamic
+    Budgeting": distance between the velocity fields of consecutive steps), in float64"""
+    a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)
+    return float(np.abs(a - b).sum() / a.size)
+
+
+def budget_schedule(l1, rho: float, dense_fraction: float = 0.2):
+    """Eq.9-11: l1 [n_prompts, n_steps] -> rho_t [n_steps].  The first floor(dense_fraction*n_steps + 0.5)
+    steps are dense (rho_t = 1); on the others l_t is the prompt average, lbar its mean over those steps,
+    alpha_t = l_t / lbar, rho_t = rho * alpha_t, capped at 1."""
+    l1 = np.atleast_2d(np.asarray(l1, np.float64))
+    n_steps = l1.shape[1]
+    n_dense = min(n_steps, int(math.floor(dense_fraction * n_steps + 0.5)))
+    out = np.ones(n_steps, np.float64)
+    if n_dense < n_steps:
+        lt = l1[:, n_dense:].mean(axis=0)
+        lbar = lt.mean()
+        alpha = lt / lbar
+        out[n_dense:] = np.minimum(1.0, rho * alpha)
+    return out
 
 
 def dense_attention(q, k, v, scale: float | None = None, q_rows=None, return_lse: bool = False):

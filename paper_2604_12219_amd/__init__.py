@@ -11,9 +11,11 @@ from .pasa import (  # noqa: F401
     attn_dense_ref,
     attn_workspace_bytes,
     block_score,
+    budget_schedule,
     forward,
     key_prior,
     kv_stats,
+    l1_distance,
     lib_path,
     load_library,
     mask_words,

@@ -17,7 +17,8 @@ _lib = None
 
 EXPORTS = ("pasa_strerror", "pasa_topk_count", "pasa_num_blocks", "pasa_mask_words", "pasa_score_workspace_bytes",
            "pasa_attn_workspace_bytes", "pasa_block_score", "pasa_route", "pasa_kv_stats", "pasa_key_prior", "pasa_sparse_attn_fwd",
-           "pasa_sparse_attn_fwd_prepared", "pasa_attn_dense_ref")
+           "pasa_sparse_attn_fwd_prepared", "pasa_attn_dense_ref", "pasa_l1_workspace_bytes", "pasa_l1_distance",
+           "pasa_budget_schedule")
 
 
 class PasaError(RuntimeError):
@@ -98,6 +99,13 @@ def load_library() -> ctypes.CDLL:
         L.pasa_kv_stats.argtypes = [vp, vp, sp, vp, ctypes.c_size_t, vp]
         L.pasa_key_prior.restype = ctypes.c_int
         L.pasa_key_prior.argtypes = [vp, vp, sp, ctypes.c_float, vp, vp, ctypes.c_size_t, vp]
+        L.pasa_l1_workspace_bytes.restype = ctypes.c_size_t
+        L.pasa_l1_workspace_bytes.argtypes = []
+        L.pasa_l1_distance.restype = ctypes.c_int
+        L.pasa_l1_distance.argtypes = [vp, vp, ctypes.c_int64, ctypes.c_int32, vp, vp, ctypes.c_size_t, vp]
+        L.pasa_budget_schedule.restype = ctypes.c_int
+        L.pasa_budget_schedule.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.c_int32, ctypes.c_int32, ctypes.c_double,
+                                           ctypes.c_double, ctypes.POINTER(ctypes.c_double)]
         L.pasa_attn_dense_ref.restype = ctypes.c_int
         L.pasa_attn_dense_ref.argtypes = [vp, vp, vp, sp, vp, vp, vp, ctypes.c_size_t, vp]
         _lib = L
@@ -190,6 +198,35 @@ def key_prior(k, v, shape: Shape, ws, eps: float = 1e-6, beta=None):
     _check(L.pasa_key_prior(_ptr(k), _ptr(v), ctypes.byref(shape.c()), eps, _ptr(beta), _ptr(ws), ws.numel(), _stream()),
            "pasa_key_prior")
     return beta
+
+
+def l1_distance(a, b, out=None, ws=None):
+    """mean |a - b| of two contiguous bf16 or fp32 device tensors of equal size -> fp32 device scalar"""
+    L = load_library()
+    if a.dtype != b.dtype or a.numel() != b.numel() or not (a.is_contiguous() and b.is_contiguous()):
+        raise ValueError("l1_distance needs two contiguous tensors of the same dtype and size")
+    dtype = {torch.bfloat16: 0, torch.float32: 1}.get(a.dtype)
+    if dtype is None:
+        raise ValueError("l1_distance supports bf16 and fp32")
+    if out is None:
+        out = torch.empty(1, dtype=torch.float32, device=a.device)
+    ws = _workspace(int(L.pasa_l1_workspace_bytes()), a.device, ws)
+    _check(L.pasa_l1_distance(_ptr(a), _ptr(b), a.numel(), dtype, _ptr(out), _ptr(ws), ws.numel(), _stream()),
+           "pasa_l1_distance")
+    return out
+
+
+def budget_schedule(l1, rho: float, dense_fraction: float = 0.2):
+    """per-step keep ratios rho_t [n_steps] from calibration signals l1 [n_prompts, n_steps] (host data)"""
+    import numpy as np
+    L = load_library()
+    l1 = np.ascontiguousarray(np.atleast_2d(np.asarray(l1, dtype=np.float64)))
+    n_prompts, n_steps = l1.shape
+    out = np.empty(n_steps, dtype=np.float64)
+    dp = ctypes.POINTER(ctypes.c_double)
+    _check(L.pasa_budget_schedule(l1.ctypes.data_as(dp), n_prompts, n_steps, float(rho), float(dense_fraction),
+                                  out.ctypes.data_as(dp)), "pasa_budget_schedule")
+    return out
 
 
 def sparse_attn_fwd(q, k, v, shape: Shape, idx, mask, out=None, lse=None, ws=None, want_lse: bool = False,

@@ -152,3 +152,21 @@ def test_generated_mfma_sequences_are_up_to_date():
 def test_sweeps_module_imports_without_a_gpu():
     import paper_2604_12219_amd.sweeps as sweeps
     assert callable(sweeps.main) and callable(sweeps.sweep_groups) and callable(sweeps.selection_histogram)
+
+
+def test_budget_schedule_host_function_matches_oracle_and_rejects_bad_input():
+    """pasa_budget_schedule is host-only: checked here without a GPU (Eq.9-11)"""
+    import numpy as np
+    import paper_2604_12219_amd as P
+    g = np.random.default_rng(5)
+    for n_prompts, n_steps, rho, dense in ((10, 50, 0.15, 0.2), (1, 7, 0.5, 0.0), (3, 33, 0.9, 0.3), (2, 5, 0.2, 1.0)):
+        l1 = g.uniform(0.1, 2.0, size=(n_prompts, n_steps))
+        np.testing.assert_allclose(P.budget_schedule(l1, rho, dense), oracle.budget_schedule(l1, rho, dense), rtol=1e-13)
+    for bad in (dict(l1=[[1.0, -1.0]], rho=0.5), dict(l1=[[0.0, 0.0]], rho=0.5, dense_fraction=0.0), dict(l1=[[1.0, 2.0]], rho=0.0),
+                dict(l1=[[1.0, float("nan")]], rho=0.5, dense_fraction=0.0), dict(l1=[[1.0, 2.0]], rho=0.5, dense_fraction=1.5)):
+        with pytest.raises(P.PasaError):
+            P.budget_schedule(**bad)
+    # the schedule drives pasa_topk_count step by step
+    r = P.budget_schedule(g.uniform(0.5, 1.5, size=(10, 50)), 0.15)
+    ks = [P.topk_count(1182, x) for x in r]
+    assert ks[:10] == [1182] * 10 and all(1 <= k <= 1182 for k in ks) and abs(sum(ks[10:]) - 0.15 * 1182 * 40) < 40

@@ -241,3 +241,21 @@ def test_forward_convenience_wrapper(P):
     torch.cuda.synchronize()
     ref = oracle.pasa_attention(to_f64(q), to_f64(k), to_f64(v), idx.cpu().numpy(), 64, group=32)
     assert_close(to_f64(out), ref, what="forward()")
+
+
+# ------------------------------------------------------------------------------------------------
+# calibration signal of the curvature-aware budget: mean L1 distance of two tensors
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n,dtype", [(1, torch.float32), (7, torch.bfloat16), (4096, torch.bfloat16), (1000003, torch.float32),
+                                     (16 * 21 * 45 * 80 + 5, torch.bfloat16), (64 * 1024 * 1024, torch.bfloat16)])
+def test_l1_distance_matches_oracle_and_is_deterministic(P, n, dtype):
+    g = torch.Generator("cuda").manual_seed(n % 1000)
+    a = torch.randn(n, device="cuda", generator=g).to(dtype)
+    b = (a.float() + 0.3 * torch.randn(n, device="cuda", generator=g)).to(dtype)
+    got = P.l1_distance(a, b)
+    again = P.l1_distance(a, b)
+    torch.cuda.synchronize()
+    want = oracle.l1_distance(a.float().cpu().numpy(), b.float().cpu().numpy())
+    assert abs(got.item() - want) <= 2e-6 * want + 1e-12
+    assert got.item() == again.item()
+    assert P.l1_distance(a, a).item() == 0.0

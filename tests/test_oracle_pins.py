@@ -469,3 +469,36 @@ def test_key_prior_special_cases():
     fro = np.linalg.norm(delta)
     want = np.array([math.log(fro * 7 / 8)] + [math.log(fro / 8)] * 7)
     np.testing.assert_allclose(oracle.key_prior(Ko[None], Vo[None], b, 8, eps=0.0)[0], want, atol=1e-9)
+
+
+# ------------------------------------------------------------------------------------------------
+# curvature-aware budget (Eq.9-11) and its L1 signal
+# ------------------------------------------------------------------------------------------------
+def test_budget_schedule_hand_example_and_invariants():
+    # 10 steps, 20 % dense -> steps 0,1 dense; signal on the sparse steps 1,1,2,4,1,1,3,3 (mean 2)
+    l1 = np.array([[9.0, 9.0, 1, 1, 2, 4, 1, 1, 3, 3]])
+    got = oracle.budget_schedule(l1, rho=0.2, dense_fraction=0.2)
+    np.testing.assert_allclose(got, [1, 1, 0.1, 0.1, 0.2, 0.4, 0.1, 0.1, 0.3, 0.3], rtol=1e-15)
+    # the paper's budget identity: the sparse densities sum to rho * |T_sparse| (no cap active)
+    g = rng(41)
+    l1 = g.uniform(0.5, 1.5, size=(10, 50))
+    r = oracle.budget_schedule(l1, 0.15)
+    assert np.all(r[:10] == 1.0) and abs(r[10:].sum() - 0.15 * 40) < 1e-12
+    # a flat signal gives the uniform budget; scaling the signal changes nothing; prompts are averaged
+    np.testing.assert_allclose(oracle.budget_schedule(np.full((3, 20), 7.0), 0.3)[4:], 0.3, rtol=1e-15)
+    np.testing.assert_allclose(oracle.budget_schedule(123.0 * l1, 0.15), r, rtol=1e-12)
+    np.testing.assert_allclose(oracle.budget_schedule(l1.mean(axis=0, keepdims=True), 0.15), r, rtol=1e-12)
+    # the cap: a spike cannot ask for more than every block
+    spike = np.ones((1, 10)); spike[0, 5] = 100.0
+    assert oracle.budget_schedule(spike, 0.5, dense_fraction=0.0).max() == 1.0
+
+
+def test_l1_distance_closed_forms():
+    g = rng(42)
+    a = g.standard_normal(1001)
+    assert oracle.l1_distance(a, a) == 0.0
+    assert abs(oracle.l1_distance(a, a + 0.25) - 0.25) < 1e-15
+    assert abs(oracle.l1_distance([1, -2, 3, 0], [0, 0, 0, 4]) - (1 + 2 + 3 + 4) / 4) < 1e-15
+    b, c = g.standard_normal(1001), g.standard_normal(1001)
+    assert oracle.l1_distance(a, b) == oracle.l1_distance(b, a)
+    assert oracle.l1_distance(a, c) <= oracle.l1_distance(a, b) + oracle.l1_distance(b, c) + 1e-15
