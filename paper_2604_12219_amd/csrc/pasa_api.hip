@@ -86,12 +86,16 @@ AttnWorkspace carve_attn(const pasa_shape_t* s) {
 
 }  // namespace
 
+#ifdef PASA_PROFILE_PHASES
 static unsigned long long* g_prof = nullptr;  // experiments only
+#endif
 
 extern "C" {
 
-// experiments only: device buffer of 32 uint64 receiving per-phase cycle sums (PASA_PROFILE_PHASES builds)
+#ifdef PASA_PROFILE_PHASES
+// experiments only, not part of the library: device buffer of 32 uint64 receiving per-phase cycle sums
 __attribute__((visibility("default"))) void pasa_debug_set_prof(void* dev_buf) { g_prof = static_cast<unsigned long long*>(dev_buf); }
+#endif
 
 const char* pasa_strerror(int status) {
   switch (status) {
@@ -256,7 +260,9 @@ static int attn_common(const void* q, const void* k, const void* v, const pasa_s
   a.stride_b = s.stride_b; a.stride_h = s.stride_h; a.stride_n = s.stride_n;
   a.bh = s.B * s.H; a.H = s.H; a.n = s.n; a.nb = nb; a.block = s.block; a.tail = s.n - (nb - 1) * s.block;
   a.scale = effective_scale(&s);
+#ifdef PASA_PROFILE_PHASES
   a.prof = g_prof;
+#endif
   a.n_slices = 1;
   if (sparse) {
     a.idx = idx; a.mask = mask; a.k_sel = k_sel; a.mask_words = (nb + 31) / 32;

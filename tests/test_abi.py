@@ -37,6 +37,11 @@ def test_every_declared_symbol_is_exported(P):
         assert hasattr(lib, n), f"{n} is declared in pasa.h but not exported"
     from paper_2604_12219_amd.pasa import EXPORTS
     assert set(EXPORTS) == set(names)
+    # ... and nothing else is: the dynamic symbol table holds exactly the declared entry points
+    import subprocess
+    out = subprocess.run(["nm", "-D", "--defined-only", P.lib_path()], capture_output=True, text=True, check=True).stdout
+    exported = {l.split()[-1] for l in out.splitlines() if " T " in l and l.split()[-1].startswith("pasa_")}
+    assert exported == set(names), exported ^ set(names)
 
 
 def test_product_has_no_cpu_fallback_and_does_not_import_the_oracle():
