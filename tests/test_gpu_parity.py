@@ -259,3 +259,45 @@ def test_l1_distance_matches_oracle_and_is_deterministic(P, n, dtype):
     assert abs(got.item() - want) <= 2e-6 * want + 1e-12
     assert got.item() == again.item()
     assert P.l1_distance(a, a).item() == 0.0
+
+
+# ------------------------------------------------------------------------------------------------
+# the whole path on a side stream and inside a HIP graph (launch-bound serving loops capture it)
+# ------------------------------------------------------------------------------------------------
+def test_forward_on_a_side_stream_and_in_a_graph_replays_identically(P):
+    q, k, v = _inputs((9, 20, 23), 2, 128, seed=21)
+    shape = P.Shape.of(q, block=64, group=32)
+    nb = P.num_blocks(shape)
+    k_sel = P.topk_count(nb, 0.15)
+    scores = torch.empty((2, nb, nb), dtype=torch.float32, device="cuda")
+    idx = torch.empty((2, nb, k_sel), dtype=torch.int32, device="cuda")
+    mask = torch.empty((2, nb, P.mask_words(nb)), dtype=torch.int32, device="cuda")
+    ws_s = torch.empty(P.score_workspace_bytes(shape), dtype=torch.uint8, device="cuda")
+    ws_a = torch.empty(P.attn_workspace_bytes(shape), dtype=torch.uint8, device="cuda")
+    out = torch.empty_like(q)
+
+    def run():
+        P.block_score(q, k, shape, scores=scores, ws=ws_s)
+        P.route(scores, k_sel, 99, 0.125, idx=idx, mask=mask)
+        P.sparse_attn_fwd(q, k, v, shape, idx, mask, out=out, ws=ws_a)
+
+    run()
+    torch.cuda.synchronize()
+    eager = out.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        out.zero_()
+        run()
+    side.synchronize()
+    assert torch.equal(out, eager)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run()
+    for _ in range(3):
+        out.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager)
+        (out.float().sum()).item()  # eager work between the replays
