@@ -324,6 +324,116 @@ def fused_step(D):
     return lines
 
 
+def run_pipe(D, mf, before, after, dmas):
+    """MFMA k of `mf` with its operand fetch issued six MFMAs ahead; `before[k]` / `after[k]` are instruction
+    lists placed right before / after MFMA k; `dmas`: tile-load instructions (slot tag, index), one per MFMA
+    shadow from the first MFMA on."""
+    lines = []
+    pipe = LdsPipe(lines, D)
+    pipe.k_addresses()
+    n = len(mf)
+    for k in range(min(pipe.nbuf, n)):
+        pipe.issue(k, mf[k]["load"])
+    dmas = list(dmas)
+    for k in range(n):
+        pipe.wait_for(k)
+        lines += before.get(k, [])
+        m = mf[k]
+        lines.append(f"{MFMA} {m['acc']}, {F(k % pipe.nbuf)}, {m['b']}, {'0' if m['first'] else m['acc']}")
+        if dmas:
+            lines.append(f"s_add_u32 m0, %[l{dmas[0][0]}], {hex(dmas[0][1] * 4096)}")
+        if k + pipe.nbuf < n:
+            pipe.issue(k + pipe.nbuf, mf[k + pipe.nbuf]["load"])
+        elif dmas:
+            lines.append("s_nop 0")
+        if dmas:
+            which, jj = dmas.pop(0)
+            lines.append(f"global_load_lds_dwordx4 %[x{jj}], %[{which}b]")
+        lines += after.get(k, [])
+    assert not dmas
+    return lines
+
+
+def flat(stream):
+    out = []
+    for item in stream:
+        out += list(item) if isinstance(item, tuple) else [item]
+    return out
+
+
+# ---- zeroth-order step of the approximation: one chunk of 32 key blocks, all of them existing and of full size ----
+#   Z = Kbar Q^T  (rows 0..31 of the statistics tile; the next tile of the stream is requested in the shadow)
+#   a_j = exp2(c z_j - m) for the unselected blocks, 0 for the selected ones; l += b sum a_j; A = sum a_j
+#   O += VS^T a   (rows 32..63), the first half of it while the second half of the a_j is still being computed
+# A selected block takes part in the running maximum: its mean-key logit cannot exceed the largest logit of
+# its keys, which the exact pass has already seen, so it never raises it.  Lane (x, h) holds block 8g + 4h + r
+# in register 4g + r, so with the bitmap word shifted right by 4h the block's bit is bit 8g + r for every lane.
+# Registers: Z v[168:183], per-element masks v[184:199], P^T v[200:207], the rest as in fused_step.
+def stats_step(D):
+    ns, nt = D // 16, D // 32
+    ni = (64 // (1024 // (2 * D))) // 4
+    n_o = 16 * nt
+    S, U, P = FS_S0, FS_S1, FS_P0
+    s = lambda i: vr(S + i)
+    u = lambda i: vr(U + i)
+    t4, t5, t7 = vr(FS_T + 4), vr(FS_T + 5), vr(FS_T + 7)
+    mf = [dict(acc=vr(S, 16), first=(st == 0), b=f"%[q{st}]", load=("k", st, 0)) for st in range(ns)]
+    for ks2 in range(2):
+        for t in range(nt):
+            mf.append(dict(acc=vr(FS_O + 16 * t, 16), first=False, b=vr(P + 4 * ks2, 4), load=("v", 2 + ks2, t)))
+    pre = [f"v_lshrrev_b32 {t5}, %[sh], %[unsel]"] + max_stream(S) + raise_max(n_o, True)
+    first_half, second_half = [], []
+    for i in range(21):  # software pipeline over the 16 elements
+        cur = first_half if i - 4 < 8 and i < 12 else second_half
+        if i < 16:
+            cur.append(f"v_fma_f32 {s(i)}, {s(i)}, %[c], -%[m]")
+            cur.append(f"v_bfe_i32 {u(i)}, {t5}, {8 * (i // 4) + i % 4}, 1")
+        if 1 <= i <= 16:
+            cur.append(f"v_exp_f32 {s(i - 1)}, {s(i - 1)}")
+        e = i - 3
+        if 0 <= e < 16:
+            cur.append(f"v_and_b32 {s(e)}, {s(e)}, {u(e)}")
+        e = i - 4
+        if 0 <= e < 16:
+            if e == 1:
+                cur.append(f"v_add_f32 {t4}, {s(0)}, {s(1)}")
+            elif e == 3:
+                cur.append(f"v_add_f32 {t7}, {s(2)}, {s(3)}")
+            elif e > 3:
+                cur.append(f"v_add_f32 {t4 if e % 2 == 0 else t7}, {t4 if e % 2 == 0 else t7}, {s(e)}")
+            if e % 2 == 1:
+                cur.append(f"v_cvt_pk_bf16_f32 {vr(P + e // 2)}, {s(e - 1)}, {s(e)}")
+    t1 = vr(FS_T + 1)
+    fin = [f"v_add_f32 {t4}, {t4}, {t7}", "s_nop 0", f"v_fmac_f32 %[l], %[bf], {t4}", f"v_mov_b32 {t1}, {t4}", "s_nop 1",
+           f"v_permlane32_swap_b32 {t4}, {t1}", "s_nop 0", f"v_add_f32 %[A], {t4}, {t1}"]
+    before = {ns: [NOP_AFTER] + flat(pre) + first_half + ["s_nop 1"], ns + nt: ["s_nop 1"]}
+    after = {}
+    spread(after, ns, ns + nt - 1, second_half)
+    spread(after, ns + nt, ns + 2 * nt - 1, fin)
+    lines = run_pipe(D, mf, before, after, [("s", j) for j in range(ni)])
+    lines.append(NOP_AFTER)
+    return lines
+
+
+# ---- first-order step: 64 value columns of one group,  O^T[part] += A ((scale Hg)^T[part] Q^T) ----
+# Rows 0..31 of the tile first, then rows 32..63 with the update from the first product in the shadow of
+# their MFMAs.  The next tile of the stream is requested in the shadow of the first MFMAs.
+def first_order_step(D, part):
+    ns = D // 16
+    ni = (64 // (1024 // (2 * D))) // 4
+    mf = []
+    for half in range(2):
+        for st in range(ns):
+            mf.append(dict(acc=vr(FS_S0 if half == 0 else FS_S1, 16), first=(st == 0), b=f"%[q{st}]", load=("k", st, half)))
+    o0, o1 = FS_O + 32 * part, FS_O + 32 * part + 16
+    after = {}
+    spread(after, ns + 1, 2 * ns - 1, [f"v_fmac_f32 {vr(o0 + r)}, %[A], {vr(FS_S0 + r)}" for r in range(16)])
+    lines = run_pipe(D, mf, {}, after, [("s", j) for j in range(ni)])
+    lines.append(NOP_AFTER)
+    lines += [f"v_fmac_f32 {vr(o1 + r)}, %[A], {vr(FS_S1 + r)}" for r in range(16)]
+    return lines
+
+
 def asm_block(lines, outs, ins, extra_clobbers=()):
     text = "\n".join(f'      "{l}\\n\\t"' for l in lines)
     clob = ", ".join([f'"v{r}"' for r in range(CLOBBER_LO, CLOBBER_HI + 1)] + [f'"{c}"' for c in extra_clobbers])
@@ -476,6 +586,32 @@ def gen():
         clob = ", ".join([f'"v{r}"' for r in range(168, 200)] + [f'"v{r}"' for r in range(216, 256)] +
                          ['"memory"', '"scc"', '"vcc"', '"m0"'])
         out.append(f"  asm volatile(\n{text}\n      : {', '.join(outs)}\n      : {', '.join(ins)}\n      : {clob});\n}}\n\n")
+    for D in (128, 64):
+        ns, nt = D // 16, D // 32
+        ni = (64 // (1024 // (2 * D))) // 4
+        dma_ins = ['[sb] "s"(sb)', '[ls] "s"(ls)'] + [f'[x{j}] "v"(x[{j}])' for j in range(ni)]
+        out.append(f"// Zeroth-order step of the approximation for a chunk of 32 existing, full key blocks.  ak, av0, av1: the\n"
+                   f"// statistics tile's address + row-fragment / column-fragment offsets; unsel: bit x set iff block x of the\n"
+                   f"// chunk is NOT selected; sh = 4 * (lane >> 5); bf = tokens per block; A <- sum of the chunk's weights a_j.\n"
+                   f"// One more tile (from sb into the slot at LDS address ls) is requested meanwhile.\n"
+                   f"PASA_DEVICE void stats_step(uint32_t ak, uint32_t av0, uint32_t av1, const bf16x8 (&q)[{ns}], f32x16 (&o)[{nt}],\n"
+                   f"                           float& m, float& l, float c, uint32_t unsel, uint32_t sh, float bf, float& A,\n"
+                   f"                           const void* sb, const uint32_t (&x)[{ni}], uint32_t ls) {{\n")
+        outs = o_ops(nt) + ['[m] "+v"(m)', '[l] "+v"(l)', '[A] "=&v"(A)']
+        ins = ['[ak] "v"(ak)', '[av0] "v"(av0)', '[av1] "v"(av1)', '[c] "s"(c)', '[unsel] "s"(unsel)', '[sh] "v"(sh)',
+               '[bf] "s"(bf)'] + q_inputs(D) + dma_ins
+        text = "\n".join(f'      "{l}\\n\\t"' for l in stats_step(D))
+        clob = ", ".join([f'"v{r}"' for r in range(FUSED_CLOBBER_LO, 256)] + ['"memory"', '"scc"', '"vcc"', '"m0"'])
+        out.append(f"  asm volatile(\n{text}\n      : {', '.join(outs)}\n      : {', '.join(ins)}\n      : {clob});\n}}\n\n")
+        for part in range(D // 64):
+            out.append(f"// First-order step: o[{2 * part}], o[{2 * part + 1}] += A * (tile x Q^T), the tile being rows {64 * part}..{64 * part + 63} of the\n"
+                       f"// group's (scale Hg)^T; a = tile address + row-fragment offset; one more tile is requested (see stats_step).\n"
+                       f"PASA_DEVICE void first_order_step{part}(uint32_t ak, const bf16x8 (&q)[{ns}], f32x16 (&o)[{nt}], float A,\n"
+                       f"                                 const void* sb, const uint32_t (&x)[{ni}], uint32_t ls) {{\n")
+            outs = [o_ops(nt)[2 * part], o_ops(nt)[2 * part + 1]]
+            ins = ['[ak] "v"(ak)', '[A] "v"(A)'] + q_inputs(D) + dma_ins
+            text = "\n".join(f'      "{l}\\n\\t"' for l in first_order_step(D, part))
+            out.append(f"  asm volatile(\n{text}\n      : {', '.join(outs)}\n      : {', '.join(ins)}\n      : {clob});\n}}\n\n")
     out.append("}  // namespace pipes\n")
     return "".join(out)
 

@@ -377,8 +377,9 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
   const uint16_t* const st = approx_on ? p.st + (int64_t)bh * p.n_chunks * 64 * D : nullptr;
   const uint16_t* const hg = approx_on ? p.hg + (int64_t)bh * p.n_groups * D * D : nullptr;
   // chunk (= bitmap word) range of this workgroup's key slice
-  const int c_lo = SPARSE ? (int)((int64_t)slice * p.n_chunks / p.n_slices) : 0;
-  const int c_hi = SPARSE ? (int)((int64_t)(slice + 1) * p.n_chunks / p.n_slices) : 0;
+  // (wave-uniform; the divisions run on the vector unit, so the results are moved to scalar registers explicitly)
+  const int c_lo = SPARSE ? __builtin_amdgcn_readfirstlane((int)((int64_t)slice * p.n_chunks / p.n_slices)) : 0;
+  const int c_hi = SPARSE ? __builtin_amdgcn_readfirstlane((int)((int64_t)(slice + 1) * p.n_chunks / p.n_slices)) : 0;
   const int qb_a = MODE == 2 ? 2 * qt : qt;
   const_u32* const mask_a = SPARSE ? (const_u32*)(p.mask + ((int64_t)bh * p.nb + qb_a) * p.mask_words) : nullptr;
   const_u32* const mask_b = (MODE == 2 && qb_a + 1 < p.nb) ? mask_a + p.mask_words : mask_a;
@@ -537,17 +538,79 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
   // ---------------- grouped approximation of the unselected blocks ----------------
   // Per chunk of 32 key blocks: its statistics tile, then for every group it intersects the HPARTS
   // tiles of the group matrix.  The tiles stream through the ring three ahead of their use, one
-  // barrier per tile; the consumer learns what a tile is from a descriptor:
-  //   bits 0-2 kind;  bits 5-12 chunk;  bits 14-25 group
+  // barrier per tile.
   const uint32_t t_approx = kProfile ? clock32() : 0u;
-  if (approx_on && c_lo < c_hi) {
+  uint32_t x_ws[NI];  // lane offsets of the loads of a workspace tile (rows of D elements)
+  dma.offsets(2 * D, 64, x_ws);
+  int c_slow = c_lo;  // first chunk left to the general loop below
+  // Groups of whole chunks (a multiple of 32 blocks), chunks whose 32 blocks all exist and are full: every chunk
+  // is the same fixed sequence of 1 + HPARTS tiles, each handled by one instruction stream that also requests
+  // the tile three further down the stream.  (The last chunk of the sequence may be short; it takes the general
+  // loop.)
+  if constexpr (SPARSE && !MULTI) {
+    const int c_fast = approx_on ? min(c_hi, p.n_chunks - 1) : 0;
+    if (c_lo < c_fast) {
+      constexpr int TPC = 1 + HPARTS;  // tiles per chunk
+      const int cpg = p.group >> 5;    // chunks per group
+      // the tile that is requested next: kind 0 = statistics of chunk rq_c, kind 1.. = that part of its group's matrix
+      int rq_c = c_lo, rq_kind = 0, rq_g = __builtin_amdgcn_readfirstlane(c_lo / cpg);  // (the division runs on the vector unit)
+      int rq_left = cpg - (c_lo - rq_g * cpg);  // chunks from rq_c to the end of its group
+      auto rq_ptr = [&]() -> const char* {
+        const uint64_t a = (uint64_t)(rq_kind == 0 ? st + (int64_t)rq_c * 64 * D : hg + ((int64_t)rq_g * D + 64 * (rq_kind - 1)) * D);
+        // wave-uniform by construction; said explicitly because the instruction streams take it in scalar registers
+        // (the intrinsic returns a signed int: back to unsigned before widening, or the low half would sign-extend)
+        const uint32_t a_lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)a);
+        const uint32_t a_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(a >> 32));
+        return reinterpret_cast<const char*>((uint64_t)a_lo | ((uint64_t)a_hi << 32));
+      };
+      // (after the last chunk: its tiles once more, into slots that nobody reads any more)
+      auto rq_advance = [&]() {
+        if (++rq_kind == TPC) {
+          rq_kind = 0;
+          if (rq_c + 1 < c_fast) {
+            ++rq_c;
+            if (--rq_left == 0) { ++rq_g; rq_left = cpg; }
+          }
+        }
+      };
+      ring_barrier<NI>(0);  // every wave is done with the ring
+      for (int i = 0; i < 3; ++i) {
+        TileDma<D>::request(rq_ptr(), x_ws, slot_wave(i));
+        rq_advance();
+      }
+      const float bf = (float)p.block;
+      const uint32_t sh = (uint32_t)(4 * h);
+      int t = 0;  // tiles consumed so far; tile t is in ring slot t & 3
+#pragma unroll 1
+      for (int chunk = c_lo; chunk < c_fast; ++chunk) {
+        float A;  // sum of the chunk's a_j: the weight of its group's first-order term
+        ring_barrier<NI>(2);
+        pipes::stats_step(slot(t) + lo.k, slot(t) + lo.v[0], slot(t) + lo.v[1], w.qf, w.o, w.m, w.l, p.c, ~mask_row[chunk], sh, bf,
+                          A, rq_ptr(), x_ws, slot_wave(t + 3));
+        rq_advance();
+        ++t;
+        ring_barrier<NI>(2);
+        pipes::first_order_step0(slot(t) + lo.k, w.qf, w.o, A, rq_ptr(), x_ws, slot_wave(t + 3));
+        rq_advance();
+        ++t;
+        if constexpr (D == 128) {
+          ring_barrier<NI>(2);
+          pipes::first_order_step1(slot(t) + lo.k, w.qf, w.o, A, rq_ptr(), x_ws, slot_wave(t + 3));
+          rq_advance();
+          ++t;
+        }
+      }
+      c_slow = c_fast;
+    }
+  }
+  // General loop: the consumer learns what a tile is from a descriptor:
+  //   bits 0-2 kind;  bits 5-12 chunk;  bits 14-25 group
+  if (approx_on && c_slow < c_hi) {
     enum : uint32_t { kEnd = 0, kStats = 3, kHPart = 4 };
-    ring_barrier<NI>(0);  // every wave is done with the ring
+    ring_barrier<NI>(0);  // every wave is done with the ring, and no request is in flight
     int issued = 0;       // tiles requested so far; tile i goes to ring slot i & 3
     int it = 0;           // tiles consumed so far
-    uint32_t x_ws[NI];  // lane offsets of the loads of a workspace tile (rows of D elements)
-    dma.offsets(2 * D, 64, x_ws);
-    int p_chunk = c_lo, p_group = 0, p_part = -1;  // p_part == -1: statistics tile next
+    int p_chunk = c_slow, p_group = 0, p_part = -1;  // p_part == -1: statistics tile next
     auto produce = [&]() -> uint32_t {
       if (p_chunk >= c_hi) return kEnd;
       uint32_t desc;
