@@ -122,6 +122,19 @@ PASA_API int pasa_route(const float* scores, int32_t BH, int32_t n_blocks, int32
                float noise_amp, int32_t* idx, uint32_t* mask, void* stream);
 
 /*
+ * Stage 2, variant -- the same routing with a Gumbel-distributed selection bias (Sec. "Stochastic Routing" asks
+ * for a random bias on the block scores and fixes no distribution; with Gumbel noise the top-k_sel of the
+ * perturbed logits is a sample without replacement from softmax(scores / temperature), the Gumbel-top-k trick).
+ *   r[bh,i,j] = fmaf(temperature, g, scores[bh,i,j]),  g = -log(-log(u)),  u = ((x >> 9) + 0.5) * 2^-23,
+ *   x the same Philox word as in pasa_route.  Order, outputs, limits and errors as in pasa_route.
+ * The two logarithms are rounded differently by different math libraries: the selection is reproducible
+ * bit for bit on this library only; against another implementation it can differ for blocks whose r lies
+ * within rounding distance of the k_sel-th largest.
+ */
+PASA_API int pasa_route_gumbel(const float* scores, int32_t BH, int32_t n_blocks, int32_t k_sel, uint64_t seed,
+                      float temperature, int32_t* idx, uint32_t* mask, void* stream);
+
+/*
  * Key/value block statistics (Eq.4's inner sum, Eq.5, Eq.12) -- the query-independent part of
  * stages 3 and 4, exported on its own so that it can be timed and reused:
  *   Kbar_j = mean_n K_{j,n},  VS_j = sum_n V_{j,n},

@@ -139,6 +139,42 @@ def route(scores_f32, k: int, seed: int, amp: float, bh_ids=None, return_noisy: 
     _load().oracle_route(_p(s, _f32p), BH, NB, int(k), int(seed) & (2**64 - 1), float(amp), _p(ids, _i32p), _p(idx, _i32p), _p(noisy, _f32p))
     return (idx, noisy) if return_noisy else idx
 
+def _philox4x32_10_np(c0, c1, c2, c3, k0, k1):
+    """Philox4x32-10 (Salmon et al., "Parallel random numbers: as easy as 1, 2, 3") on numpy arrays of counters;
+    written out in 64-bit integer arithmetic, independently of the C routine above (a pin compares the two)."""
+    M0, M1, W0, W1, MASK = 0xD2511F53, 0xCD9E8D57, 0x9E3779B9, 0xBB67AE85, 0xFFFFFFFF
+    c0, c1, c2, c3 = (np.asarray(c, np.uint64) & np.uint64(MASK) for c in np.broadcast_arrays(c0, c1, c2, c3))
+    k0, k1 = int(k0) & MASK, int(k1) & MASK
+    for _ in range(10):
+        p0 = np.uint64(M0) * c0
+        p1 = np.uint64(M1) * c2
+        hi0, lo0 = p0 >> np.uint64(32), p0 & np.uint64(MASK)
+        hi1, lo1 = p1 >> np.uint64(32), p1 & np.uint64(MASK)
+        c0, c1, c2, c3 = hi1 ^ c1 ^ np.uint64(k0), lo1, hi0 ^ c3 ^ np.uint64(k1), lo0
+        k0, k1 = (k0 + W0) & MASK, (k1 + W1) & MASK
+    return c0, c1, c2, c3
+
+
+def route_gumbel(scores_f32, k: int, seed: int, temperature: float, bh_ids=None, return_noisy: bool = False):
+    """Routing with a Gumbel-distributed selection bias (Sec. "Stochastic Routing" fixes no distribution; this is
+    the Gumbel-top-k variant): r = s + temperature * g, g = -log(-log(u)), u = ((x >> 9) + 0.5) 2^-23 with x the
+    Philox word of (bh, i, j) exactly as in route(); the k largest r per row (ties: smaller j), ascending.
+    fp64 after the binary32 scores.  -> idx [BH, NB, k] int32 (and r)."""
+    s = _c(scores_f32, np.float32).astype(np.float64)
+    BH, NB, NB2 = s.shape
+    assert NB == NB2 and 1 <= k <= NB
+    seed = int(seed) & (2**64 - 1)
+    bh = np.arange(BH) if bh_ids is None else np.asarray(bh_ids)
+    j = np.arange(NB)
+    words = _philox4x32_10_np((j >> 2)[None, None, :], np.arange(NB)[None, :, None], bh[:, None, None], 0,
+                              seed & 0xFFFFFFFF, seed >> 32)
+    x = np.choose((j & 3)[None, None, :], words)  # word j & 3 of the call that serves blocks 4(j>>2) .. +3
+    u = ((x >> np.uint64(9)).astype(np.float64) + 0.5) * 2.0**-23
+    r = s + float(temperature) * -np.log(-np.log(u))
+    order = np.lexsort((np.broadcast_to(j, r.shape), -r), axis=-1)  # larger r first, then smaller j
+    idx = np.sort(order[..., :k], axis=-1).astype(np.int32)
+    return (idx, r) if return_noisy else idx
+
 
 def kv_stats(k, v, block: int, group: int, want_hj: bool = False):
     """Returns dict(kbar, vs, hg[, hj]); hg is None when group <= 0."""

@@ -159,8 +159,8 @@ int pasa_block_score(const void* q, const void* k, const pasa_shape_t* shape, co
   return pasa_launch_block_score(p, static_cast<hipStream_t>(stream)) == hipSuccess ? PASA_OK : PASA_EHIP;
 }
 
-int pasa_route(const float* scores, int32_t BH, int32_t n_blocks, int32_t k_sel, uint64_t seed, float noise_amp,
-               int32_t* idx, uint32_t* mask, void* stream) {
+static int route_impl(const float* scores, int32_t BH, int32_t n_blocks, int32_t k_sel, uint64_t seed, float noise_amp,
+                      int gumbel, int32_t* idx, uint32_t* mask, void* stream) {
   if (!scores || !idx || BH < 1 || n_blocks < 1) return PASA_EINVAL;
   if (k_sel < 1 || k_sel > n_blocks) return PASA_EINVAL;
   if (!(noise_amp >= 0.f) || isinf(noise_amp)) return PASA_EINVAL;
@@ -170,8 +170,19 @@ int pasa_route(const float* scores, int32_t BH, int32_t n_blocks, int32_t k_sel,
   p.bh = BH; p.nb = n_blocks; p.k_sel = k_sel; p.mask_words = (n_blocks + 31) / 32;
   p.seed_lo = (uint32_t)(seed & 0xffffffffu); p.seed_hi = (uint32_t)(seed >> 32);
   p.amp = noise_amp;
+  p.gumbel = gumbel;
   p.idx = idx; p.mask = mask;
   return pasa_launch_route(p, static_cast<hipStream_t>(stream)) == hipSuccess ? PASA_OK : PASA_EHIP;
+}
+
+int pasa_route(const float* scores, int32_t BH, int32_t n_blocks, int32_t k_sel, uint64_t seed, float noise_amp,
+               int32_t* idx, uint32_t* mask, void* stream) {
+  return route_impl(scores, BH, n_blocks, k_sel, seed, noise_amp, 0, idx, mask, stream);
+}
+
+int pasa_route_gumbel(const float* scores, int32_t BH, int32_t n_blocks, int32_t k_sel, uint64_t seed, float temperature,
+                      int32_t* idx, uint32_t* mask, void* stream) {
+  return route_impl(scores, BH, n_blocks, k_sel, seed, temperature, 1, idx, mask, stream);
 }
 
 // validation shared by the statistics and attention entry points; fills `s` (group normalised)

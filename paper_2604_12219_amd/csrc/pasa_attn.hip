@@ -551,7 +551,8 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
     const int c_fast = approx_on ? min(c_hi, p.n_chunks - 1) : 0;
     if (c_lo < c_fast) {
       constexpr int TPC = 1 + HPARTS;  // tiles per chunk
-      const int cpg = p.group >> 5;    // chunks per group
+      // chunks per group (a group size that is not a multiple of 32 is the single group that spans all blocks)
+      const int cpg = (p.group & 31) == 0 ? p.group >> 5 : p.n_chunks;
       // the tile that is requested next: kind 0 = statistics of chunk rq_c, kind 1.. = that part of its group's matrix
       int rq_c = c_lo, rq_kind = 0, rq_g = __builtin_amdgcn_readfirstlane(c_lo / cpg);  // (the division runs on the vector unit)
       int rq_left = cpg - (c_lo - rq_g * cpg);  // chunks from rq_c to the end of its group

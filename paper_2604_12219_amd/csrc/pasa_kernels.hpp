@@ -72,6 +72,7 @@ struct RouteParams {
   int32_t bh, nb, k_sel, mask_words;
   uint32_t seed_lo, seed_hi;
   float amp;
+  int32_t gumbel;  // 0: uniform bias in [-amp, amp); 1: Gumbel(0, amp) bias
   int32_t* idx;
   uint32_t* mask;  // nullable
 };

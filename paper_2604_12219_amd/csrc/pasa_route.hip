@@ -7,6 +7,7 @@
 //      k are chosen; the ascending index list and the selection bitmap are emitted with
 //      ballot + prefix popcount, so the output order needs no sort.
 // Integer work throughout except the single fused multiply-add, hence bit-reproducible on a CPU.
+// (The Gumbel variant of the bias takes two logarithms and is reproducible only up to their rounding.)
 #include "pasa_kernels.hpp"
 
 namespace {
@@ -54,7 +55,13 @@ __global__ void __launch_bounds__(64 * kWavesPerGroup) route_kernel(RouteParams 
       const int j = 4 * q4 + e;
       uint32_t key = 0u;  // padding ranks below every real key (real keys are never 0: see ordered_key)
       if (j < nb) {
-        const float w = (float)((int32_t)x[e] >> 8) * 0x1p-23f;
+        float w;
+        if (p.gumbel) {  // u in (0,1) on a 2^-23 grid, exact in binary32; standard Gumbel variate -log(-log u)
+          const float u = ((float)(x[e] >> 9) + 0.5f) * 0x1p-23f;
+          w = -logf(-logf(u));
+        } else {
+          w = (float)((int32_t)x[e] >> 8) * 0x1p-23f;
+        }
         key = ordered_key(__fmaf_rn(p.amp, w, srow[j]));
       }
       keys[j] = key;

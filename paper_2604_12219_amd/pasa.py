@@ -16,7 +16,7 @@ _LIB_PATH = os.path.join(_HERE, "libpasa_hip.so")
 _lib = None
 
 EXPORTS = ("pasa_strerror", "pasa_topk_count", "pasa_num_blocks", "pasa_mask_words", "pasa_score_workspace_bytes",
-           "pasa_attn_workspace_bytes", "pasa_block_score", "pasa_route", "pasa_kv_stats", "pasa_key_prior", "pasa_sparse_attn_fwd",
+           "pasa_attn_workspace_bytes", "pasa_block_score", "pasa_route", "pasa_route_gumbel", "pasa_kv_stats", "pasa_key_prior", "pasa_sparse_attn_fwd",
            "pasa_sparse_attn_fwd_prepared", "pasa_attn_dense_ref", "pasa_l1_workspace_bytes", "pasa_l1_distance",
            "pasa_budget_schedule")
 
@@ -90,6 +90,9 @@ def load_library() -> ctypes.CDLL:
         L.pasa_block_score.argtypes = [vp, vp, sp, vp, vp, vp, ctypes.c_size_t, vp]
         L.pasa_route.restype = ctypes.c_int
         L.pasa_route.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_uint64, ctypes.c_float,
+                                 vp, vp, vp]
+        L.pasa_route_gumbel.restype = ctypes.c_int
+        L.pasa_route_gumbel.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_uint64, ctypes.c_float,
                                  vp, vp, vp]
         L.pasa_sparse_attn_fwd.restype = ctypes.c_int
         L.pasa_sparse_attn_fwd.argtypes = [vp, vp, vp, sp, vp, vp, ctypes.c_int32, vp, vp, vp, ctypes.c_size_t, vp]
@@ -169,16 +172,19 @@ def block_score(q, k, shape: Shape, key_bias=None, scores=None, ws=None):
     return scores
 
 
-def route(scores, k_sel: int, seed: int, noise_amp: float, idx=None, mask=None, want_mask: bool = True):
-    """-> (idx int32 [BH, N_B, k_sel] ascending, mask int32-typed bitmap [BH, N_B, ceil(N_B/32)] or None)"""
+def route(scores, k_sel: int, seed: int, noise_amp: float, idx=None, mask=None, want_mask: bool = True, noise: str = "uniform"):
+    """-> (idx int32 [BH, N_B, k_sel] ascending, mask int32-typed bitmap [BH, N_B, ceil(N_B/32)] or None)
+    noise: "uniform" (bias in [-noise_amp, noise_amp), bit-reproducible) or "gumbel" (Gumbel(0, noise_amp) bias)"""
+    if noise not in ("uniform", "gumbel"):
+        raise ValueError(f"unknown routing noise {noise!r}")
     L = load_library()
     BH, nb, _ = scores.shape
     if idx is None:
         idx = torch.empty((BH, nb, max(k_sel, 1)), dtype=torch.int32, device=scores.device)
     if mask is None and want_mask:
         mask = torch.empty((BH, nb, (nb + 31) // 32), dtype=torch.int32, device=scores.device)
-    _check(L.pasa_route(_ptr(scores), BH, nb, k_sel, seed & (2**64 - 1), noise_amp, _ptr(idx), _ptr(mask), _stream()),
-           "pasa_route")
+    fn = L.pasa_route if noise == "uniform" else L.pasa_route_gumbel
+    _check(fn(_ptr(scores), BH, nb, k_sel, seed & (2**64 - 1), noise_amp, _ptr(idx), _ptr(mask), _stream()), "pasa_route")
     return idx, mask
 
 

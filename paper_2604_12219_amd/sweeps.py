@@ -95,7 +95,8 @@ def selection_histogram(workload: str, n_steps: int, noise_amp: float):
     w = workloads.WORKLOADS[workload]
     bits = torch.arange(32, device="cuda", dtype=torch.int32)
     counts = {}
-    for label, amp in (("deterministic", 0.0), ("stochastic", noise_amp)):
+    for label, amp, kind in (("deterministic", 0.0, "uniform"), ("stochastic, uniform bias", noise_amp, "uniform"),
+                             ("stochastic, Gumbel bias", noise_amp / 2, "gumbel")):
         total = None
         for step in range(n_steps):
             a = workloads.budget_schedule_noise_amplitude(step, n_steps)
@@ -104,7 +105,7 @@ def selection_histogram(workload: str, n_steps: int, noise_amp: float):
             nb = P.num_blocks(shape)
             k_sel = P.topk_count(nb, workloads.budget_schedule_keep_ratio(step, n_steps))
             scores = P.block_score(q, k, shape)
-            _, m = P.route(scores, k_sel, w.seed + step, amp)
+            _, m = P.route(scores, k_sel, w.seed + step, amp, noise=kind)
             sel = ((m[..., None] >> bits) & 1).reshape(m.shape[0], nb, -1)[..., :nb]  # [BH, query block, key block]
             total = sel.to(torch.int32) if total is None else total + sel
         counts[label] = total.float()

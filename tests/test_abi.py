@@ -30,7 +30,7 @@ def declared_symbols():
 
 def test_every_declared_symbol_is_exported(P):
     names = declared_symbols()
-    assert {"pasa_block_score", "pasa_route", "pasa_sparse_attn_fwd", "pasa_attn_dense_ref", "pasa_kv_stats",
+    assert {"pasa_block_score", "pasa_route", "pasa_route_gumbel", "pasa_sparse_attn_fwd", "pasa_attn_dense_ref", "pasa_kv_stats",
             "pasa_sparse_attn_fwd_prepared", "pasa_topk_count", "pasa_strerror"} <= set(names)
     lib = ctypes.CDLL(P.lib_path())
     for n in names:

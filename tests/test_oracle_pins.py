@@ -502,3 +502,63 @@ def test_l1_distance_closed_forms():
     b, c = g.standard_normal(1001), g.standard_normal(1001)
     assert oracle.l1_distance(a, b) == oracle.l1_distance(b, a)
     assert oracle.l1_distance(a, c) <= oracle.l1_distance(a, b) + oracle.l1_distance(b, c) + 1e-15
+
+# ---- Gumbel variant of the routing bias ----------------------------------------------------------------------
+
+def test_numpy_philox_agrees_with_the_c_routine_and_the_published_vectors():
+    rng = np.random.default_rng(3)
+    for _ in range(50):
+        ctr = rng.integers(0, 2**32, 4, dtype=np.uint64)
+        key = rng.integers(0, 2**32, 2, dtype=np.uint64)
+        got = [int(x) for x in oracle._philox4x32_10_np(*ctr, *key)]
+        assert got == [int(x) for x in oracle.philox4x32_10(ctr.astype(np.uint32), key.astype(np.uint32))]
+    # Random123's known-answer vector for the all-ones counter and key
+    ones = 0xFFFFFFFF
+    assert [int(x) for x in oracle._philox4x32_10_np(ones, ones, ones, ones, ones, ones)] == \
+        [0x408F276D, 0x41C83B0E, 0xA20BC7C6, 0x6D5451FD]
+
+
+def test_gumbel_routing_uses_the_same_philox_word_as_the_uniform_bias():
+    """route() with zero scores and amplitude 1 returns w = ((int32)x >> 8) 2^-23; route_gumbel's u is built from
+    x >> 9 of the same word, so floor((w 2^23 mod 2^24) / 2) must be u 2^23 - 0.5"""
+    s = np.zeros((2, 9, 9), np.float32)
+    _, w = oracle.route(s, 1, 0xABCDEF0123, 1.0, return_noisy=True)
+    _, r = oracle.route_gumbel(s, 1, 0xABCDEF0123, 1.0, return_noisy=True)
+    top24 = np.mod(np.round(w.astype(np.float64) * 2**23).astype(np.int64), 2**24)
+    u = np.exp(-np.exp(-r))
+    np.testing.assert_allclose(u * 2**23 - 0.5, top24 // 2, atol=1e-6)
+    assert (u > 0).all() and (u < 1).all()
+
+
+def test_gumbel_zero_temperature_is_deterministic_topk():
+    rng = np.random.default_rng(5)
+    s = rng.standard_normal((2, 17, 17)).astype(np.float32)
+    np.testing.assert_array_equal(oracle.route_gumbel(s, 5, 99, 0.0), oracle.route(s, 5, 99, 0.0))
+
+
+def test_gumbel_top1_samples_the_softmax_and_top2_the_plackett_luce_law():
+    """Gumbel-max: argmax_j (s_j + tau g_j) ~ softmax(s / tau); the top-k set is a sample without replacement"""
+    logits = np.array([0.3, -0.4, 1.1, 0.0])
+    tau = 0.7
+    BH = 6000
+    s = np.broadcast_to(logits.astype(np.float32), (BH, 4, 4)).copy()
+    p = np.exp(logits.astype(np.float32).astype(np.float64) / tau)
+    p /= p.sum()
+    n = BH * 4
+    top1 = oracle.route_gumbel(s, 1, 2024, tau).reshape(-1)
+    freq = np.bincount(top1, minlength=4) / n
+    assert np.abs(freq - p).max() < 4.5 * np.sqrt(0.25 / n)
+    top2 = oracle.route_gumbel(s, 2, 2025, tau).reshape(-1, 2)
+    for a in range(4):
+        for b in range(a + 1, 4):
+            want = p[a] * p[b] / (1 - p[a]) + p[b] * p[a] / (1 - p[b])
+            got = np.mean((top2[:, 0] == a) & (top2[:, 1] == b))
+            assert abs(got - want) < 4.5 * np.sqrt(0.25 / n), (a, b, got, want)
+
+
+def test_gumbel_variates_have_the_textbook_moments():
+    s = np.zeros((4, 64, 64), np.float32)
+    _, g = oracle.route_gumbel(s, 1, 7, 1.0, return_noisy=True)
+    n = g.size
+    assert abs(g.mean() - 0.5772156649) < 5 * np.sqrt(np.pi**2 / 6 / n)
+    assert abs(g.var() - np.pi**2 / 6) < 0.1
