@@ -247,31 +247,53 @@ PASA_DEVICE void ring_barrier(int newer) {
 // ---- walking a selection bitmap ------------------------------------------------------------------
 // Yields, in ascending order, the key blocks whose bit is set in a combination of (up to) two bitmap
 // rows, within a range of 32-bit words.  MODE 0: blocks in both rows; 1: in row a only; 2: in row b
-// only; 3: row a as it is.  All state is wave-uniform; the word after the current one is requested
-// one word early so that the scalar load is off the critical path.
+// only; 3: row a as it is.  The rows are held in registers, a window of 64 words (2048 key blocks) at a
+// time: lane i keeps word (window + i), a ballot says which words are not empty, and the next block is
+// two find-first-set steps and a lane read away -- no memory access and no loop over empty words on the
+// way from one block to the next.  (With the words fetched from memory as they were needed, the scalar
+// load's latency sat in front of every tile step that moved on to a new word.)  The yielded values are
+// wave-uniform.
 template <int MODE>
 struct BitWalk {
   const_u32* ra;
   const_u32* rb;
-  int wi, w_end;
-  uint32_t cur, nxt;
-  PASA_DEVICE uint32_t word(int i) const {
-    const uint32_t a = ra[i];
-    if constexpr (MODE == 3) return a;
-    const uint32_t b = rb[i];
-    return MODE == 0 ? (a & b) : MODE == 1 ? (a & ~b) : (b & ~a);
+  int w_lo, w_end;  // word range of the walk
+  int win;          // first word of the window in registers
+  uint32_t words;   // per lane: the combined word (win + lane), zero outside the range
+  uint64_t nz;      // lanes of the window whose word still has to be visited
+  uint32_t cur;     // bits of the current word that are still to be yielded
+  int wi;           // index of the current word
+  PASA_DEVICE void load_window(int lane) {
+    const int i = win + lane;
+    uint32_t x = 0u;
+    if (i >= w_lo && i < w_end) {
+      const uint32_t a = ra[i];
+      if constexpr (MODE == 3) {
+        x = a;
+      } else {
+        const uint32_t b = rb[i];
+        x = MODE == 0 ? (a & b) : MODE == 1 ? (a & ~b) : (b & ~a);
+      }
+    }
+    words = x;
+    nz = __builtin_amdgcn_ballot_w64(x != 0u);
   }
-  PASA_DEVICE void init(const_u32* a, const_u32* b, int w0, int w1) {
-    ra = a; rb = b; wi = w0; w_end = w1;
-    cur = w0 < w1 ? word(w0) : 0u;
-    nxt = w0 + 1 < w1 ? word(w0 + 1) : 0u;
+  PASA_DEVICE void init(const_u32* a, const_u32* b, int w0, int w1, int lane) {
+    ra = a; rb = b; w_lo = w0; w_end = w1;
+    win = w0; cur = 0u; wi = w0;
+    load_window(lane);
   }
-  PASA_DEVICE int next() {  // kNoBlock when exhausted (and on every later call)
-    while (cur == 0u) {
-      if (wi + 1 >= w_end) return kNoBlock;
-      ++wi;
-      cur = nxt;
-      nxt = wi + 1 < w_end ? word(wi + 1) : 0u;
+  PASA_DEVICE int next(int lane) {  // kNoBlock when exhausted (and on every later call)
+    if (cur == 0u) {
+      while (nz == 0ull) {
+        if (win + 64 >= w_end) return kNoBlock;
+        win += 64;
+        load_window(lane);
+      }
+      const int l = __builtin_ctzll(nz);
+      nz &= nz - 1ull;
+      wi = win + l;
+      cur = (uint32_t)__builtin_amdgcn_readlane((int)words, l);
     }
     const int j = __builtin_ctz(cur);
     cur &= cur - 1u;
@@ -407,8 +429,8 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
     BitWalk<MODE == 2 ? 0 : 3> walk;
     int blk = kNoBlock, sub = 0, dense_next = 0;
     if constexpr (SPARSE) {
-      walk.init(mask_a, mask_b, c_lo, c_hi);
-      blk = walk.next();
+      walk.init(mask_a, mask_b, c_lo, c_hi, lane);
+      blk = walk.next(lane);
     }
     auto plan = [&]() -> int {  // first row of the next tile, or -1
       if constexpr (MODE == 0) {
@@ -417,12 +439,12 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
       } else if constexpr (MODE == 1) {  // two tiles per 128-token block
         if (blk == kNoBlock) return -1;
         const int r0 = blk * 128 + sub * 64;
-        if (++sub == 2) { sub = 0; blk = walk.next(); }
+        if (++sub == 2) { sub = 0; blk = walk.next(lane); }
         return r0;
       } else {
         if (blk == kNoBlock) return -1;
         const int r0 = blk * 64;
-        blk = walk.next();
+        blk = walk.next(lane);
         return r0;
       }
     };
@@ -473,9 +495,9 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
   if constexpr (MODE == 2) {
     BitWalk<1> only_a;
     BitWalk<2> only_b;
-    only_a.init(mask_a, mask_b, c_lo, c_hi);
-    only_b.init(mask_a, mask_b, c_lo, c_hi);
-    int a_blk = only_a.next(), b_blk = only_b.next();
+    only_a.init(mask_a, mask_b, c_lo, c_hi, lane);
+    only_b.init(mask_a, mask_b, c_lo, c_hi, lane);
+    int a_blk = only_a.next(lane), b_blk = only_b.next(lane);
     const uint32_t t0 = kProfile ? clock32() : 0u;
     if (a_blk != kNoBlock || b_blk != kNoBlock) {
       ring_barrier<NI>(0);  // every wave is done with the ring
@@ -489,7 +511,7 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
 #pragma unroll 1
       while (whole(a_blk) && whole(b_blk)) {
         ring_barrier<NI>(0);  // the K tiles have landed; the V slots are free
-        const int a_nxt = only_a.next(), b_nxt = only_b.next();
+        const int a_nxt = only_a.next(lane), b_nxt = only_b.next(lane);
         const int a_rq2 = a_nxt != kNoBlock ? a_nxt : b_nxt != kNoBlock ? b_nxt : a_blk;
         const int b_rq2 = b_nxt != kNoBlock ? b_nxt : a_rq2;
         bf16x8 pf[4];
@@ -513,8 +535,8 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
         const bool read_b = second ? have_b : !have_a;  // whose slots this wave reads
         const uint32_t k_tile = slot(read_b ? 2 : 0), v_tile = slot(read_b ? 3 : 1);
         const int a_req = have_a ? a_blk : b_blk, b_req = have_b ? b_blk : a_blk;
-        const int a_nxt = have_a ? only_a.next() : kNoBlock;
-        const int b_nxt = have_b ? only_b.next() : kNoBlock;
+        const int a_nxt = have_a ? only_a.next(lane) : kNoBlock;
+        const int b_nxt = have_b ? only_b.next(lane) : kNoBlock;
         const int a_rq2 = a_nxt != kNoBlock ? a_nxt : b_nxt != kNoBlock ? b_nxt : a_req;
         const int b_rq2 = b_nxt != kNoBlock ? b_nxt : a_rq2;
         const int t_row = my_blk != kNoBlock ? tile_row(my_blk * 64) : 0;
