@@ -28,14 +28,16 @@ def _sample_blocks(nb, rng, extra=4):
     return sorted(fixed)
 
 
-@pytest.mark.parametrize("name,heads_checked", [("wan1.3b-480p", (0, 11)), ("wan14b-720p", (0, 39)), ("long-video", (17,))])
+@pytest.mark.parametrize("name,heads_checked", [("wan1.3b-480p", (0, 11)), ("wan14b-720p", (0, 39)), ("long-video", (17,)),
+                                                ("long-video-b64", (1,))])
 def test_full_size_workload_sampled_against_oracle(P, name, heads_checked):
     w = workloads.WORKLOADS[name]
     q, k, v = workloads.make_workload_qkv(w, device="cuda")
     shape = P.Shape.of(q, block=w.block, group=32)
     nb = P.num_blocks(shape)
     k_sel = P.topk_count(nb, w.keep_ratio)
-    assert (nb, k_sel) == {"wan1.3b-480p": (512, 102), "wan14b-720p": (1182, 177), "long-video": (1154, 58)}[name]
+    assert (nb, k_sel) == {"wan1.3b-480p": (512, 102), "wan14b-720p": (1182, 177), "long-video": (1154, 58),
+                             "long-video-b64": (2307, 69)}[name]
     scores = P.block_score(q, k, shape)
     idx, mask = P.route(scores, k_sel, w.seed, NOISE_AMP)
     out, lse = P.sparse_attn_fwd(q, k, v, shape, idx, mask, want_lse=True)

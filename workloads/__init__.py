@@ -51,6 +51,9 @@ WORKLOADS = {
     "wan14b-720p": Workload("wan14b-720p", (21, 45, 80), heads=40, d=128, block=64, keep_ratio=0.15),
     # long video: 41 latent frames at the 720p grid, coarse blocks, very sparse
     "long-video": Workload("long-video", (41, 45, 80), heads=40, d=128, block=128, keep_ratio=0.05),
+    # the same token count with 64-token blocks: 2307 key blocks, i.e. selection bitmaps of more than 64 words (two heads
+    # only: a parity case, not a benchmark)
+    "long-video-b64": Workload("long-video-b64", (41, 45, 80), heads=2, d=128, block=64, keep_ratio=0.03),
 }
 
 
