@@ -2,12 +2,14 @@
  * pasa.h -- C ABI of the MI355X (gfx950) implementation of the PASA sparse self-attention forward
  * ("Ride the Wave: Precision-Allocated Sparse Attention for Smooth Video Generation").
  *
- * The forward runs in four stages, each an entry point of its own so that a caller (and a checker)
- * can see every intermediate:
+ * The forward runs in stages, each an entry point of its own so that a caller (and a checker) can see
+ * every intermediate:
  *
  *   pasa_block_score      block-pooled Q/K routing logits             (Eq.8 without its row softmax)
  *   pasa_key_prior        optional covariance prior of the routing logits (Eq.8, second term)
  *   pasa_route            seeded stochastic top-k block selection     (Eq.2 + Sec. "Stochastic Routing")
+ *   pasa_route_gumbel     the same selection with a Gumbel-distributed bias (a variant)
+ *   pasa_kv_stats         key/value block statistics, the query-independent part (Eq.4, Eq.5, Eq.12)
  *   pasa_sparse_attn_fwd  exact attention over the selected blocks + grouped Taylor approximation
  *                         of the unselected ones under one normaliser (Eq.7, Eq.4, Eq.5, Eq.12, Eq.14)
  *   pasa_attn_dense_ref   dense attention with the same tile machinery (Eq.1)
