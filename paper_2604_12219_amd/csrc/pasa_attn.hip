@@ -12,10 +12,12 @@
 // in-lane reductions plus one exchange with lane ^ 32.
 //
 // Work decomposition.  A workgroup is 4 waves = 128 query rows: one query block of 128 tokens, or
-// TWO ADJACENT query blocks of 64 tokens (waves 0,1 and waves 2,3).  In the second case the
-// workgroup walks the UNION of the two ascending block lists; a tile is staged in LDS once and each
-// wave pair computes on it only if its own list contains the block.  Adjacent query blocks of a
-// video select heavily overlapping key blocks, so this cuts the K/V traffic per query block.
+// TWO ADJACENT query blocks of 64 tokens (waves 0,1 and waves 2,3).  In the second case the key
+// blocks that both query blocks selected are handled first, every tile serving all four waves
+// (adjacent query blocks of a video select heavily overlapping key blocks, so this cuts the K/V
+// traffic per query block); then the blocks that only one of the two selected, each wave pair on
+// a tile of its own at the same time; then the approximation of the unselected blocks.  An online
+// softmax does not care in which order the keys arrive.
 //
 // Key-range slicing (sparse path, long sequences).  L2 misses of all XCDs share one fabric whose read
 // bandwidth is far below what the eight L2s deliver on hits, and one head's K and V are much larger
@@ -26,8 +28,12 @@
 // and a small second kernel merges the partial results of a row.
 //
 // Data movement.  All tiles (K, V, block statistics, group matrices) are 64-row tiles that stream
-// through a ring of four LDS buffers by direct global->LDS loads, requested three tiles ahead of
-// their use; one workgroup barrier per tile.
+// through a ring of four 16 KB LDS buffers by direct global->LDS loads: the exact passes consume a
+// (K, V) pair per step while the next pair lands in the other two buffers, the approximation pass
+// one tile per step with the requests three tiles ahead; one workgroup barrier per step (two in
+// the pass that works on two different tiles at once).  The MFMA sequences with their operand
+// fetches, and the softmax arithmetic in their shadow, are the generated instruction streams of
+// pasa_mfma_pipes.hpp.
 #include "pasa_device.hpp"
 #include "pasa_kernels.hpp"
 #include "pasa_mfma_pipes.hpp"
@@ -39,7 +45,6 @@ constexpr float kLn2 = 0.6931471805599453f;
 constexpr int kXcds = 8;    // accelerator complex dies of an MI355X, each with its own L2
 constexpr int kWaves = 4;   // waves per workgroup
 constexpr int kRing = 4;    // LDS tile buffers
-constexpr int kAhead = 3;   // a tile is requested this many tiles before it is consumed
 constexpr int kNoBlock = 0x7fffffff;
 #ifdef PASA_PROFILE_PHASES
 constexpr bool kProfile = true;      // per-phase cycle counts into AttnParams::prof
