@@ -182,6 +182,7 @@ def main():
         torch.cuda.synchronize()
         dense_ms = e0.elapsed_time(e1) / reps
 
+    traffic = MEASURED_TRAFFIC_BYTES.get((w.name, args.group)) if args.kv_slices in (0, 1) and not args.with_prior else None
     result = {
         "metric": "dense-equivalent TFLOP/s of one PASA sparse-attention call (4*B*H*n^2*d / time); ms per call in ms_per_step",
         "value": dense_equiv_tflops,
@@ -207,7 +208,8 @@ def main():
         "roofline": {"kernel": "attn_kernel (sparse: exact tiles + grouped approximation)", "bound": "mfma",
                      "achieved": attn_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, args.group)),
+                     "traffic": traffic,
+                     "traffic_rate_TBps": (traffic / (attn_ms * 1e-3) / 1e12) if traffic else None,
                      "avg_launch_ms": attn_ms, "flops_per_launch": fl["attn"]},
         "paper_context": "paper reports end-to-end video latency only (8x H800): PASA 2.19x over dense at Wan 2.1-14B 720p",
     }
