@@ -29,7 +29,7 @@ def _sample_blocks(nb, rng, extra=4):
 
 
 @pytest.mark.parametrize("name,heads_checked", [("wan1.3b-480p", (0, 11)), ("wan14b-720p", (0, 39)), ("long-video", (17,)),
-                                                ("long-video-b64", (1,))])
+                                                ("long-video-b64", (1,)), ("hunyuan13b-720p", (23,))])
 def test_full_size_workload_sampled_against_oracle(P, name, heads_checked):
     w = workloads.WORKLOADS[name]
     q, k, v = workloads.make_workload_qkv(w, device="cuda")
@@ -37,7 +37,7 @@ def test_full_size_workload_sampled_against_oracle(P, name, heads_checked):
     nb = P.num_blocks(shape)
     k_sel = P.topk_count(nb, w.keep_ratio)
     assert (nb, k_sel) == {"wan1.3b-480p": (512, 102), "wan14b-720p": (1182, 177), "long-video": (1154, 58),
-                             "long-video-b64": (2307, 69)}[name]
+                             "long-video-b64": (2307, 69), "hunyuan13b-720p": (1857, 279)}[name]
     scores = P.block_score(q, k, shape)
     idx, mask = P.route(scores, k_sel, w.seed, NOISE_AMP)
     out, lse = P.sparse_attn_fwd(q, k, v, shape, idx, mask, want_lse=True)

@@ -49,6 +49,9 @@ WORKLOADS = {
     "wan1.3b-480p": Workload("wan1.3b-480p", (21, 30, 52), heads=12, d=128, block=64, keep_ratio=0.20),
     # Wan 2.1 14B at 720p: 21 latent frames x 45 x 80 patches = 75,600 tokens
     "wan14b-720p": Workload("wan14b-720p", (21, 45, 80), heads=40, d=128, block=64, keep_ratio=0.15),
+    # the paper's second model family, HunyuanVideo 13B at 720p.  The paper gives no shapes for it; these are assumed from
+    # the public model description (24 heads of 128; 129 frames -> 33 latent frames x 45 x 80 patches, video tokens only)
+    "hunyuan13b-720p": Workload("hunyuan13b-720p", (33, 45, 80), heads=24, d=128, block=64, keep_ratio=0.15),
     # long video: 41 latent frames at the 720p grid, coarse blocks, very sparse
     "long-video": Workload("long-video", (41, 45, 80), heads=40, d=128, block=128, keep_ratio=0.05),
     # the same token count with 64-token blocks: 2307 key blocks, i.e. selection bitmaps of more than 64 words (two heads
