@@ -1,8 +1,11 @@
 // Stage 2 of the PASA forward on gfx950: per-row top-k block selection with a seeded stochastic
 // bias (Eq.2; Sec. "Stochastic Routing").  One wavefront per (head, query block) row:
 //   1. r_j = fmaf(amp, w_j, s_j) with w_j from Philox4x32-10 (one call serves 4 consecutive j),
-//      mapped to an order-preserving uint32 key (-0 folded onto +0) and kept in LDS;
-//   2. the k-th largest key is found by a 32-step bitwise search, each step a ballot count;
+//      mapped to an order-preserving uint32 key (-0 folded onto +0); the keys pass through LDS once
+//      and then stay in registers, key block lane + 64 t in register t;
+//   2. the k-th largest key is found by a bitwise search from the top bit down; a step counts the keys
+//      that reach the candidate (per-lane counts, summed by one ballot per bit of the count) and the
+//      search stops as soon as exactly k keys do;
 //   3. keys above the threshold are selected, ties at the threshold are taken in ascending j until
 //      k are chosen; the ascending index list and the selection bitmap are emitted with
 //      ballot + prefix popcount, so the output order needs no sort.
@@ -36,20 +39,30 @@ __device__ __forceinline__ uint32_t ordered_key(float r) {
 
 constexpr int kWavesPerGroup = 4;
 
+// KPL = keys per lane: the row is padded to 64 * KPL keys.
+template <int KPL>
 __global__ void __launch_bounds__(64 * kWavesPerGroup) route_kernel(RouteParams p) {
-  extern __shared__ uint32_t keys_all[];  // [kWavesPerGroup][nb_pad]
+  extern __shared__ __attribute__((aligned(16))) uint32_t keys_all[];  // [kWavesPerGroup][64 * KPL]
+  static_assert(KPL % 4 == 0, "a lane writes whole quads of keys");
+  constexpr int NB_PAD = 64 * KPL;
+  constexpr int CNT_BITS = KPL < 8 ? 3 : KPL < 16 ? 4 : KPL < 32 ? 5 : KPL < 64 ? 6 : 7;  // a lane's count is at most KPL
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t row = (int64_t)blockIdx.x * kWavesPerGroup + wave;
   if (row >= (int64_t)p.bh * p.nb) return;  // whole wave leaves; no workgroup barrier is used below
-  const int nb = p.nb, nb_pad = (nb + 63) & ~63;
-  uint32_t* keys = keys_all + wave * nb_pad;
+  const int nb = p.nb;
+  uint32_t* keys = keys_all + wave * NB_PAD;
   const uint32_t bh = (uint32_t)(row / nb), i = (uint32_t)(row % nb);
   const float* srow = p.scores + row * nb;
 
-  // 1. noisy keys; lane handles key blocks 4*(lane + 64*t) .. +3
-  for (int q4 = lane; q4 * 4 < nb_pad; q4 += 64) {
-    uint32_t x[4];
-    philox4x32_10((uint32_t)q4, i, bh, 0u, p.seed_lo, p.seed_hi, x);
+  // 1. noisy keys; one Philox call serves key blocks 4 q4 .. 4 q4 + 3, so lane handles those of q4 = lane + 64 t.
+  //    They pass through LDS once, to regroup them as j = lane + 64 t for what follows.
+#pragma unroll
+  for (int t = 0; t < (KPL + 3) / 4; ++t) {
+    const int q4 = lane + 64 * t;  // 4 q4 + 3 < 64 KPL: KPL is a multiple of 4
+    uint32_t x[4] = {0u, 0u, 0u, 0u};
+    if (4 * q4 < nb) philox4x32_10((uint32_t)q4, i, bh, 0u, p.seed_lo, p.seed_hi, x);
+    uint4 kq;
+    uint32_t* ke = reinterpret_cast<uint32_t*>(&kq);
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const int j = 4 * q4 + e;
@@ -64,24 +77,39 @@ __global__ void __launch_bounds__(64 * kWavesPerGroup) route_kernel(RouteParams 
         }
         key = ordered_key(__fmaf_rn(p.amp, w, srow[j]));
       }
-      keys[j] = key;
+      ke[e] = key;
     }
+    *reinterpret_cast<uint4*>(keys + 4 * q4) = kq;
   }
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  uint32_t key[KPL];  // key[t] belongs to key block lane + 64 t
+#pragma unroll
+  for (int t = 0; t < KPL; ++t) key[t] = keys[lane + 64 * t];
 
-  // 2. largest T with #{key >= T} >= k
+  // wave-wide number of keys that satisfy a predicate: per-lane count, then one ballot per bit of the count
+  auto wave_count = [&](auto pred) -> int {
+    uint32_t c = 0u;
+#pragma unroll
+    for (int t = 0; t < KPL; ++t) c += pred(key[t]) ? 1u : 0u;
+    int total = 0;
+#pragma unroll
+    for (int b = 0; b < CNT_BITS; ++b) total += (int)__popcll(__ballot((c >> b) & 1u)) << b;
+    return total;
+  };
+
+  // 2. largest T with #{key >= T} >= k, bit by bit from the top.  As soon as exactly k keys reach a candidate,
+  //    the selection is settled (those k keys) and the remaining bits do not matter.
   const int k = p.k_sel;
   uint32_t T = 0u;
   for (int bit = 31; bit >= 0; --bit) {
     const uint32_t cand = T | (1u << bit);
-    int cnt = 0;
-    for (int j = lane; j < nb_pad; j += 64) cnt += __popcll(__ballot(keys[j] >= cand));
+    const int cnt = wave_count([&](uint32_t x) { return x >= cand; });
     if (cnt >= k) T = cand;
+    if (cnt == k) break;
   }
-  int above = 0;
-  for (int j = lane; j < nb_pad; j += 64) above += __popcll(__ballot(keys[j] > T));
+  const int above = wave_count([&](uint32_t x) { return x > T; });
   int ties_left = k - above;  // how many keys equal to T are still to be taken, in ascending j
 
   // 3. emit
@@ -89,11 +117,13 @@ __global__ void __launch_bounds__(64 * kWavesPerGroup) route_kernel(RouteParams 
   uint32_t* mrow = p.mask ? p.mask + row * p.mask_words : nullptr;
   const uint64_t lt = (1ull << lane) - 1ull;
   int written = 0;
-  for (int j0 = 0; j0 < nb_pad; j0 += 64) {
-    const uint32_t key = keys[j0 + lane];
-    const uint64_t tie_b = __ballot(key == T);
+#pragma unroll
+  for (int t = 0; t < KPL; ++t) {
+    const int j0 = 64 * t;
+    if (j0 >= ((nb + 63) & ~63)) break;
+    const uint64_t tie_b = __ballot(key[t] == T);
     const int tie_rank = __popcll(tie_b & lt);
-    const bool sel = (key > T) || (key == T && tie_rank < ties_left);
+    const bool sel = (key[t] > T) || (key[t] == T && tie_rank < ties_left);
     const uint64_t sel_b = __ballot(sel);
     if (sel) out[written + __popcll(sel_b & lt)] = j0 + lane;
     written += __popcll(sel_b);
@@ -105,13 +135,26 @@ __global__ void __launch_bounds__(64 * kWavesPerGroup) route_kernel(RouteParams 
   }
 }
 
+template <int KPL>
+hipError_t launch_route(const RouteParams& p, hipStream_t stream) {
+  const int64_t rows = (int64_t)p.bh * p.nb;
+  const size_t lds = (size_t)kWavesPerGroup * 64 * KPL * sizeof(uint32_t);
+  const unsigned grid = (unsigned)((rows + kWavesPerGroup - 1) / kWavesPerGroup);
+  hipLaunchKernelGGL(route_kernel<KPL>, dim3(grid), dim3(64 * kWavesPerGroup), lds, stream, p);
+  return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t pasa_launch_route(const RouteParams& p, hipStream_t stream) {
-  const int64_t rows = (int64_t)p.bh * p.nb;
-  const int nb_pad = (p.nb + 63) & ~63;
-  const size_t lds = (size_t)kWavesPerGroup * nb_pad * sizeof(uint32_t);
-  const unsigned grid = (unsigned)((rows + kWavesPerGroup - 1) / kWavesPerGroup);
-  hipLaunchKernelGGL(route_kernel, dim3(grid), dim3(64 * kWavesPerGroup), lds, stream, p);
-  return hipGetLastError();
+  const int kpl = (p.nb + 63) / 64;  // at most kRouteMaxBlocks / 64
+  if (kpl <= 4) return launch_route<4>(p, stream);
+  if (kpl <= 8) return launch_route<8>(p, stream);
+  if (kpl <= 12) return launch_route<12>(p, stream);
+  if (kpl <= 16) return launch_route<16>(p, stream);
+  if (kpl <= 20) return launch_route<20>(p, stream);
+  if (kpl <= 24) return launch_route<24>(p, stream);
+  if (kpl <= 32) return launch_route<32>(p, stream);
+  if (kpl <= 48) return launch_route<48>(p, stream);
+  return launch_route<64>(p, stream);
 }

@@ -97,7 +97,8 @@ def test_key_prior_matches_oracle_and_feeds_the_scores(P, grid, d, block, group)
 # stage 2: routing is bit-exact against the oracle fed the GPU's scores
 # ------------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("nb,k_sel,amp", [(16, 4, 0.0), (16, 4, 0.5), (67, 9, 1.0), (130, 130, 0.3), (515, 77, 2.0),
-                                          (1182, 177, 0.7), (64, 1, 0.1)])
+                                          (1182, 177, 0.7), (64, 1, 0.1), (1000, 150, 0.3), (1500, 1500, 0.1),
+                                          (2000, 3, 0.2), (4096, 300, 0.5)])
 def test_routing_bit_exact(P, nb, k_sel, amp):
     g = torch.Generator("cuda").manual_seed(nb)
     scores = torch.randn((3, nb, nb), device="cuda", generator=g)
