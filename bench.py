@@ -24,7 +24,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
 # HBM-side bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # command (scaled by a plain copy of known size; see profiles/attn_kernel_wan14b-720p_hbm_counters.txt).
 # Measured, not computed here: null for workloads without a committed counter run.
-MEASURED_TRAFFIC_BYTES = {("wan14b-720p", 32): 171.6e9 + 0.774e9}
+MEASURED_TRAFFIC_BYTES = {("wan14b-720p", 32): 170.1e9 + 0.774e9}
 NOISE_AMP_DEFAULT = 0.125       # logit units: calibrated once on the 480p workload (~15 % of selections change)
 
 
