@@ -117,6 +117,10 @@ def test_argument_validation_returns_before_any_launch(P):
     assert route(k=0) == EINVAL and route(k=17) == EINVAL
     assert route(amp=-1.0) == EINVAL and route(amp=float("inf")) == EINVAL
     assert route(nb=1 << 20, k=4) == EUNSUPPORTED
+    assert L.pasa_route_gumbel(None, 2, 16, 4, 7, ctypes.c_float(0.5), fake, None, None) == EINVAL
+    assert L.pasa_route_gumbel(fake, 2, 16, 0, 7, ctypes.c_float(0.5), fake, None, None) == EINVAL
+    assert L.pasa_route_gumbel(fake, 2, 16, 4, 7, ctypes.c_float(-0.5), fake, None, None) == EINVAL
+    assert L.pasa_route_gumbel(fake, 2, 1 << 20, 4, 7, ctypes.c_float(0.5), fake, None, None) == EUNSUPPORTED
 
     def sparse(shape, q=fake, idx=fake, mask=fake, k=4, out=ctypes.c_void_p(0x2000), ws=fake, nbytes=big):
         return L.pasa_sparse_attn_fwd(q, fake, fake, ctypes.byref(shape), idx, mask, k, out, None, ws, nbytes, None)
