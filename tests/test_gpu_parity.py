@@ -198,6 +198,31 @@ CASES = [
 ]
 
 
+def test_sparse_path_respects_strides_batch_and_scale(P):
+    """Q, K, V and O as views of token-major storage [B, n, H, d + pad] (what a transformer block hands over),
+    batch 2, a non-default logit scale: every stage reads through the strides of the shape"""
+    q, k, v = _inputs((5, 21, 13), 3, 128, seed=13, batch=2)
+    B, H, n, d = q.shape
+    big = torch.zeros((4, B, n, H, d + 8), dtype=torch.bfloat16, device="cuda")
+    for i, t in enumerate((q, k, v)):
+        big[i, :, :, :, :d] = t.permute(0, 2, 1, 3)
+    qs, ks, vs, out = (big[i, :, :, :, :d].permute(0, 2, 1, 3) for i in range(4))
+    scale = 0.07
+    shape = P.Shape.of(qs, block=64, group=32, scale=scale)
+    nb = P.num_blocks(shape)
+    k_sel = P.topk_count(nb, 0.2)
+    scores = P.block_score(qs, ks, shape)
+    idx, mask = P.route(scores, k_sel, 77, 0.2)
+    P.sparse_attn_fwd(qs, ks, vs, shape, idx, mask, out=out)
+    torch.cuda.synchronize()
+    ref_scores = oracle.block_scores(to_f64(q), to_f64(k), 64, scale=scale)
+    np.testing.assert_allclose(scores.cpu().numpy(), ref_scores, atol=1e-3 * np.abs(ref_scores).max(), rtol=0)
+    np.testing.assert_array_equal(idx.cpu().numpy(), oracle.route(scores.cpu().numpy(), k_sel, 77, 0.2))
+    res = oracle.pasa_attention(to_f64(q), to_f64(k), to_f64(v), idx.cpu().numpy(), 64, group=32, scale=scale)
+    assert_close(to_f64(out), res, what="strided sparse path")
+    assert torch.all(big[3, :, :, :, d:] == 0)  # the padding between rows was not written
+
+
 @pytest.mark.parametrize("grid,heads,d,block,group,keep", CASES)
 def test_sparse_matches_oracle(P, grid, heads, d, block, group, keep):
     q, k, v = _inputs(grid, heads, d, seed=7)
