@@ -198,6 +198,21 @@ CASES = [
 ]
 
 
+@pytest.mark.parametrize("block", [64, 128])
+@pytest.mark.parametrize("n", [1, 2, 63, 64, 65, 127, 128, 129, 191, 192, 193, 257, 320])
+def test_sequence_lengths_around_tile_and_block_boundaries(P, n, block):
+    """every length around a multiple of 64 and of 128, dense and sparse (one of two, or two of three blocks kept)"""
+    q, k, v = _inputs((1, 1, n), 1, 128, seed=n)
+    shape = P.Shape.of(q, block=block, group=32)
+    out = P.attn_dense_ref(q, k, v, shape)
+    torch.cuda.synchronize()
+    assert_close(to_f64(out), oracle.dense_attention(to_f64(q), to_f64(k), to_f64(v)), what=f"dense n={n}")
+    out, lse, idx = _run_sparse(P, q, k, v, block, 32, 0.6)
+    res = oracle.pasa_attention(to_f64(q), to_f64(k), to_f64(v), idx.cpu().numpy(), block, group=32, return_all=True)
+    assert_close(to_f64(out), res["o"], what=f"sparse n={n} b={block}")
+    np.testing.assert_allclose(lse.cpu().numpy(), res["lse"], atol=2e-2)
+
+
 def test_sparse_path_respects_strides_batch_and_scale(P):
     """Q, K, V and O as views of token-major storage [B, n, H, d + pad] (what a transformer block hands over),
     batch 2, a non-default logit scale: every stage reads through the strides of the shape"""
