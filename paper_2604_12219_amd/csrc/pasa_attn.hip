@@ -570,14 +570,13 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
   uint32_t x_ws[NI];  // lane offsets of the loads of a workspace tile (rows of D elements)
   dma.offsets(2 * D, 64, x_ws);
   int c_slow = c_lo;  // first chunk left to the general loop below
-  // Groups of whole chunks (a multiple of 32 blocks), chunks whose 32 blocks all exist and are full: every chunk
-  // is the same fixed sequence of 1 + HPARTS tiles, each handled by one instruction stream that also requests
-  // the tile three further down the stream.  (The last chunk of the sequence may be short; it takes the general
-  // loop.)
+  // Groups of whole chunks (a multiple of 32 blocks), chunks whose 32 blocks all exist and are full: a fixed
+  // sequence of tiles (the statistics of a group's chunks, then the HPARTS tiles of its matrix), each handled by
+  // one instruction stream that also requests the tile three further down the stream.  (The last chunk of the
+  // sequence may be short; it takes the general loop.)
   if constexpr (SPARSE && !MULTI) {
     const int c_fast = approx_on ? min(c_hi, p.n_chunks - 1) : 0;
     if (c_lo < c_fast) {
-      constexpr int TPC = 1 + HPARTS;  // tiles per chunk
       // chunks per group (a group size that is not a multiple of 32 is the single group that spans all blocks)
       const int cpg = (p.group & 31) == 0 ? p.group >> 5 : p.n_chunks;
       // the tile that is requested next: kind 0 = statistics of chunk rq_c, kind 1.. = that part of its group's matrix
@@ -591,11 +590,28 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
         const uint32_t a_hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(a >> 32));
         return reinterpret_cast<const char*>((uint64_t)a_lo | ((uint64_t)a_hi << 32));
       };
-      // (after the last chunk: its tiles once more, into slots that nobody reads any more)
+      // The group matrix follows the statistics of the LAST chunk of its group (and of the last chunk of this loop,
+      // should the group go on beyond it): the first-order term is linear in the group weight, so the weights of a
+      // group's chunks are summed and the matrix is applied once.
+      // (after the last tile: the last chunk's statistics over and over, into slots that nobody reads any more)
+      bool rq_done = false;
       auto rq_advance = [&]() {
-        if (++rq_kind == TPC) {
+        if (rq_done) return;
+        const bool last_chunk = rq_c + 1 >= c_fast;
+        if (rq_kind == 0) {
+          if (rq_left == 1 || last_chunk) {
+            rq_kind = 1;  // the group's matrix follows
+          } else {        // the next chunk belongs to the same group
+            ++rq_c;
+            --rq_left;
+          }
+        } else if (rq_kind < HPARTS) {
+          ++rq_kind;
+        } else {
           rq_kind = 0;
-          if (rq_c + 1 < c_fast) {
+          if (last_chunk) {
+            rq_done = true;
+          } else {
             ++rq_c;
             if (--rq_left == 0) { ++rq_g; rq_left = cpg; }
           }
@@ -609,24 +625,30 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
       const float bf = (float)p.block;
       const uint32_t sh = (uint32_t)(4 * h);
       int t = 0;  // tiles consumed so far; tile t is in ring slot t & 3
+      float A_group = 0.f;                       // sum of the a_j of the group's chunks so far: the weight of its first-order term
+      int left = cpg - (c_lo - (c_lo / cpg) * cpg);  // chunks from `chunk` to the end of its group
 #pragma unroll 1
       for (int chunk = c_lo; chunk < c_fast; ++chunk) {
-        float A;  // sum of the chunk's a_j: the weight of its group's first-order term
+        float A;
         ring_barrier<NI>(2);
         pipes::stats_step(slot(t) + lo.k, slot(t) + lo.v[0], slot(t) + lo.v[1], w.qf, w.o, w.m, w.l, p.c, ~mask_row[chunk], sh, bf,
                           A, rq_ptr(), x_ws, slot_wave(t + 3));
         rq_advance();
         ++t;
+        A_group += A;
+        if (--left != 0 && chunk + 1 < c_fast) continue;
+        left = cpg;
         ring_barrier<NI>(2);
-        pipes::first_order_step0(slot(t) + lo.k, w.qf, w.o, A, rq_ptr(), x_ws, slot_wave(t + 3));
+        pipes::first_order_step0(slot(t) + lo.k, w.qf, w.o, A_group, rq_ptr(), x_ws, slot_wave(t + 3));
         rq_advance();
         ++t;
         if constexpr (D == 128) {
           ring_barrier<NI>(2);
-          pipes::first_order_step1(slot(t) + lo.k, w.qf, w.o, A, rq_ptr(), x_ws, slot_wave(t + 3));
+          pipes::first_order_step1(slot(t) + lo.k, w.qf, w.o, A_group, rq_ptr(), x_ws, slot_wave(t + 3));
           rq_advance();
           ++t;
         }
+        A_group = 0.f;
       }
       c_slow = c_fast;
     }
