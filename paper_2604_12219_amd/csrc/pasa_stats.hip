@@ -135,7 +135,8 @@ __global__ void __launch_bounds__(256) hg_finish_kernel(StatsParams p) {
   const float f = p.scale / (float)blocks_in_group;
   const float* part = p.partial + (int64_t)bh * p.n_units * D * D;
   uint16_t* out = p.hg + ((int64_t)bh * p.n_groups + g) * D * D;
-  for (int x = threadIdx.x; x < D * D / 8; x += 256) {  // 8 consecutive key columns of one value column
+  // 8 consecutive key columns of one value column per thread; the grid's z dimension covers the matrix
+  for (int x = threadIdx.x + 256 * blockIdx.z; x < D * D / 8; x += 256 * gridDim.z) {
     const int d_out = x % D, d_in0 = (x / D) * 8;
     bf16x8 v;
 #pragma unroll
@@ -275,7 +276,9 @@ __global__ void __launch_bounds__(256) key_prior_kernel(StatsParams p, float eps
 }  // namespace
 
 hipError_t pasa_launch_kv_stats(const StatsParams& p, hipStream_t stream) {
-  dim3 g1(p.n_units, p.bh), g2(p.n_groups, p.bh);
+  // few groups (long groups, or one global matrix): spread each matrix over several workgroups
+  const int split = (int64_t)p.n_groups * p.bh < 2048 ? p.d * p.d / 8 / 256 : 1;
+  dim3 g1(p.n_units, p.bh), g2(p.n_groups, p.bh, split);
   if (p.d == 128) {
     hipLaunchKernelGGL(kv_stats_kernel<128>, g1, dim3(256), 0, stream, p);
     hipLaunchKernelGGL(hg_finish_kernel<128>, g2, dim3(256), 0, stream, p);
