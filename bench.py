@@ -43,15 +43,20 @@ def algorithmic_flops(B, H, n, d, block, group, k_sel):
 
 
 def cpu_baseline(w, q, k, v, k_sel, noise_amp, group, target_seconds=20.0):
-    """Time the fp64 oracle (its own scoring, routing and attention) on head 0 and a strided subset of
-    query blocks sized for roughly `target_seconds`."""
+    """Time the fp64 oracle (its own scoring, routing, statistics and attention) on a sample sized for roughly
+    `target_seconds`: a strided subset of the query blocks of head 0 if a whole head takes longer than that,
+    otherwise as many whole heads as fit."""
     import numpy as np
     import oracle
-    q0, k0, v0 = (t[0, 0:1].float().cpu().numpy().astype(np.float64) for t in (q, k, v))
     nb = w.n_blocks
+
+    def head(h):
+        return tuple(t[0, h:h + 1].float().cpu().numpy().astype(np.float64) for t in (q, k, v))
+
+    q0, k0, v0 = head(0)
     t0 = time.perf_counter()
     s = oracle.block_scores(q0, k0, w.block).astype(np.float32)
-    idx = oracle.route(s, k_sel, w.seed, noise_amp)
+    idx = oracle.route(s, k_sel, w.seed, noise_amp, bh_ids=[0])
     t_route = time.perf_counter() - t0
     # time the head's statistics alone, probe a few query blocks, then size the sample to the time target
     t0 = time.perf_counter()
@@ -72,11 +77,24 @@ def cpu_baseline(w, q, k, v, k_sel, noise_amp, group, target_seconds=20.0):
     rows = sum(min(w.block, w.n - j * w.block) for j in blocks)
     frac = rows / w.n
     total = t_route * frac + t_attn  # scoring/routing cost scaled to the sampled share of the head
-    dense_equiv = 4.0 * w.n * w.n * w.d * frac / total / 1e12
+    per_head = t_route + t_stats + (t_attn - t_stats) / frac
+    heads_done = frac
+    sample = (f"head 0 of {w.heads}, {len(blocks)} of {nb} query blocks (stride {stride}, tail block included), "
+              f"full-head statistics and routing")
+    if stride == 1:  # a whole head fits the budget: add whole heads (each with its own scoring and routing)
+        extra = int(min(w.heads - 1, max(0, round((target_seconds - total) / per_head))))
+        for h in range(1, 1 + extra):
+            qh, kh, vh = head(h)
+            t0 = time.perf_counter()
+            sh = oracle.block_scores(qh, kh, w.block).astype(np.float32)
+            ih = oracle.route(sh, k_sel, w.seed, noise_amp, bh_ids=[h])
+            oracle.pasa_attention(qh, kh, vh, ih, w.block, group=group)
+            total += time.perf_counter() - t0
+        heads_done = 1 + extra
+        sample = f"heads 0..{extra} of {w.heads}, every query block, each head with its own scoring, routing and statistics"
+    dense_equiv = 4.0 * w.n * w.n * w.d * heads_done / total / 1e12
     return dict(value=dense_equiv, unit="TFLOP/s (dense-equivalent)", cores=oracle.num_threads(), kind="oracle",
-                sample=f"head 0 of {w.heads}, {len(blocks)} of {nb} query blocks (stride {stride}, tail block included), "
-                       f"full-head statistics and routing; {total:.1f} s",
-                seconds=total, seconds_per_head_extrapolated=(t_route + t_stats + (t_attn - t_stats) / frac))
+                sample=f"{sample}; {total:.1f} s", seconds=total, seconds_per_head_extrapolated=per_head)
 
 
 def main():
