@@ -270,23 +270,23 @@ struct BitWalk {
   int wi;           // index of the current word
   PASA_DEVICE void load_window(int lane) {
     const int i = win + lane;
-    uint32_t x = 0u;
+    uint32_t a = 0u, b = 0u;
     if (i >= w_lo && i < w_end) {
-      const uint32_t a = ra[i];
-      if constexpr (MODE == 3) {
-        x = a;
-      } else {
-        const uint32_t b = rb[i];
-        x = MODE == 0 ? (a & b) : MODE == 1 ? (a & ~b) : (b & ~a);
-      }
+      a = ra[i];
+      if constexpr (MODE != 3) b = rb[i];
     }
-    words = x;
-    nz = __builtin_amdgcn_ballot_w64(x != 0u);
+    combine(a, b);
   }
-  PASA_DEVICE void init(const_u32* a, const_u32* b, int w0, int w1, int lane) {
+  PASA_DEVICE void combine(uint32_t a, uint32_t b) {
+    words = MODE == 3 ? a : MODE == 0 ? (a & b) : MODE == 1 ? (a & ~b) : (b & ~a);
+    nz = __builtin_amdgcn_ballot_w64(words != 0u);
+  }
+  // first_a, first_b: word (w0 + lane) of the two rows, zero at and beyond w1 (fetched once by the caller for all
+  // the walks over the same rows)
+  PASA_DEVICE void init(const_u32* a, const_u32* b, int w0, int w1, uint32_t first_a, uint32_t first_b) {
     ra = a; rb = b; w_lo = w0; w_end = w1;
     win = w0; cur = 0u; wi = w0;
-    load_window(lane);
+    combine(first_a, first_b);
   }
   PASA_DEVICE int next(int lane) {  // kNoBlock when exhausted (and on every later call)
     if (cur == 0u) {
@@ -378,17 +378,24 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
   const int q_row = qt * 128 + wave * 32 + ql;
 
   WaveState<D> w;
+  // The queries are fetched together with the first tile pair (below): the two latencies overlap.
+  auto load_q = [&]() {
 #pragma unroll
-  for (int s = 0; s < D / 16; ++s) {
-    uint4 raw = {0u, 0u, 0u, 0u};
-    if (q_row < n) raw = *reinterpret_cast<const uint4*>(qb + (int64_t)q_row * p.stride_n + 16 * s + 8 * h);
-    w.qf[s] = __builtin_bit_cast(bf16x8, raw);
-  }
+    for (int s = 0; s < D / 16; ++s) {
+      uint4 raw = {0u, 0u, 0u, 0u};
+      if (q_row < n) raw = *reinterpret_cast<const uint4*>(qb + (int64_t)q_row * p.stride_n + 16 * s + 8 * h);
+      w.qf[s] = __builtin_bit_cast(bf16x8, raw);
+    }
+  };
   // Have the query loads land here.  Otherwise the compiler, which cannot see the tile loads written in
   // assembly, waits for "all loads" at the first use of Q inside the tile loops, in every iteration, and
   // so also for the tiles that were requested just before -- the prefetch would never overlap the math.
+  // (Its wait covers the tile loads requested between the query loads and this point as well; the first
+  // step of the tile loop needs those anyway.)
+  auto settle_q = [&]() {
 #pragma unroll
-  for (int s = 0; s < D / 16; ++s) asm volatile("" : "+v"(w.qf[s]));
+    for (int s = 0; s < D / 16; ++s) asm volatile("" : "+v"(w.qf[s]));
+  };
 #pragma unroll
   for (int t = 0; t < D / 32; ++t) w.o[t] = f32x16{0};
   w.m = -INFINITY;
@@ -411,6 +418,14 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
   const_u32* const mask_a = SPARSE ? (const_u32*)(p.mask + ((int64_t)bh * p.nb + qb_a) * p.mask_words) : nullptr;
   const_u32* const mask_b = (MODE == 2 && qb_a + 1 < p.nb) ? mask_a + p.mask_words : mask_a;
   const_u32* const mask_row = second ? mask_b : mask_a;  // this wave's own row
+  // the first 64 words of the two rows, lane i word c_lo + i: every walk below starts from them
+  uint32_t first_a = 0u, first_b = 0u;
+  if constexpr (SPARSE) {
+    if (c_lo + lane < c_hi) {
+      first_a = mask_a[c_lo + lane];
+      first_b = mask_b[c_lo + lane];
+    }
+  }
 
   // Tile requests.  The tile for key rows [r0, r0 + 64) is fetched from row tile_row(r0) on: shifted
   // back where it would reach beyond the last token, so that all 64 rows exist (r0 may even lie beyond
@@ -434,7 +449,7 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
     BitWalk<MODE == 2 ? 0 : 3> walk;
     int blk = kNoBlock, sub = 0, dense_next = 0;
     if constexpr (SPARSE) {
-      walk.init(mask_a, mask_b, c_lo, c_hi, lane);
+      walk.init(mask_a, mask_b, c_lo, c_hi, first_a, first_b);
       blk = walk.next(lane);
     }
     auto plan = [&]() -> int {  // first row of the next tile, or -1
@@ -454,7 +469,9 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
       }
     };
     int r_cur = plan();
+    load_q();
     if (r_cur >= 0) { request(kb, r_cur, 0); request(vb, r_cur, 1); }
+    settle_q();
     int pair = 0;
     // Tiles whose 64 rows are all keys of the tile: one instruction stream per tile.  (Tiles come in ascending
     // order, so a tile that reaches beyond the last token can only be among the last ones.)
@@ -500,8 +517,8 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
   if constexpr (MODE == 2) {
     BitWalk<1> only_a;
     BitWalk<2> only_b;
-    only_a.init(mask_a, mask_b, c_lo, c_hi, lane);
-    only_b.init(mask_a, mask_b, c_lo, c_hi, lane);
+    only_a.init(mask_a, mask_b, c_lo, c_hi, first_a, first_b);
+    only_b.init(mask_a, mask_b, c_lo, c_hi, first_a, first_b);
     int a_blk = only_a.next(lane), b_blk = only_b.next(lane);
     const uint32_t t0 = kProfile ? clock32() : 0u;
     if (a_blk != kNoBlock || b_blk != kNoBlock) {
