@@ -21,6 +21,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
+HBM_PEAK_BYTES_PER_S = 8.0e12   # MI355X HBM3E
 # HBM-side bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # command (scaled by a plain copy of known size; see profiles/attn_kernel_wan14b-720p_hbm_counters.txt).
 # Measured, not computed here: null for workloads without a committed counter run.
@@ -110,6 +111,7 @@ def main():
                     help="route on the full logit of Eq.8: statistics first, then the covariance prior as key bias (not the default path)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-mfma-probe", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain device copy of Q (known size) so that hardware byte counters can be scaled")
@@ -180,6 +182,7 @@ def main():
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
     stage_ms = [sum(e[s].elapsed_time(e[s + 1]) for e in ev) / n_ev for s in range(4)]
+    call_ms = sorted(e[0].elapsed_time(e[4]) for e in ev)  # per call, events on the stream
     attn_ms = stage_ms[3]
 
     fl = algorithmic_flops(w.batch, w.heads, w.n, w.d, w.block, args.group, k_sel)
@@ -200,7 +203,20 @@ def main():
         torch.cuda.synchronize()
         dense_ms = e0.elapsed_time(e1) / reps
 
+    qkv_bytes = w.batch * w.heads * w.n * w.d * 2
+    score_bytes = bh * nb * nb * 4
+    stage_bytes = {"block_score": 2 * qkv_bytes + score_bytes + 2 * bh * nb * w.d * 4,
+                   "route": score_bytes + bh * nb * (k_sel + P.mask_words(nb)) * 4,
+                   "kv_stats": 2 * qkv_bytes + (bh * (nb + 31) // 32 * 64 * w.d * 2 if args.group else 0)}
+    stage_hbm = {name: {"algorithmic_GB": stage_bytes[name] / 1e9,
+                        "achieved_TBps": stage_bytes[name] / (stage_ms[i] * 1e-3) / 1e12,
+                        "frac_of_8TBps": stage_bytes[name] / (stage_ms[i] * 1e-3) / HBM_PEAK_BYTES_PER_S}
+                 for i, name in enumerate(("block_score", "route", "kv_stats"))} if not args.with_prior else None
+    # bytes of K/V tiles the attention kernel asks for if no tile were reused between query blocks
+    tile_bytes = bh * nb * k_sel * 2 * w.block * w.d * 2
     traffic = MEASURED_TRAFFIC_BYTES.get((w.name, args.group)) if args.kv_slices in (0, 1) and not args.with_prior else None
+    # what a loop of nothing but MFMAs reaches on this device right now (the published peak assumes 2.4 GHz)
+    mfma_loop = None if args.no_mfma_probe else P.mfma_probe()
     result = {
         "metric": "dense-equivalent TFLOP/s of one PASA sparse-attention call (4*B*H*n^2*d / time); ms per call in ms_per_step",
         "value": dense_equiv_tflops,
@@ -217,7 +233,10 @@ def main():
         "config": {"workload": w.name, "B": w.batch, "H": w.heads, "n": w.n, "d": w.d, "block": w.block,
                    "keep_ratio": w.keep_ratio, "k_sel": k_sel, "n_blocks": nb, "group": args.group,
                    "noise_amp": args.noise_amp, "seed": w.seed, "kv_slices": args.kv_slices, "covariance_prior": args.with_prior},
+        "ms_per_call_median": call_ms[len(call_ms) // 2], "ms_per_call_min": call_ms[0],
         "stage_ms": {"block_score": stage_ms[0], "route": stage_ms[1], "kv_stats": stage_ms[2], "sparse_attn": attn_ms},
+        # the HBM-bound stages against the 8 TB/s peak: algorithmic bytes (inputs read once, outputs written once) / time
+        "stage_hbm": stage_hbm,
         "computed_tflops": computed_tflops,
         "algorithmic_tflop": {kk: vv / 1e12 for kk, vv in fl.items()},
         "dense_ref_ms": dense_ms,
@@ -228,7 +247,9 @@ def main():
                      "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS,
                      "traffic": traffic,
                      "traffic_rate_TBps": (traffic / (attn_ms * 1e-3) / 1e12) if traffic else None,
-                     "avg_launch_ms": attn_ms, "flops_per_launch": fl["attn"]},
+                     "avg_launch_ms": attn_ms, "flops_per_launch": fl["attn"],
+                     "unshared_tile_TBps": tile_bytes / (attn_ms * 1e-3) / 1e12,
+                     "mfma_loop_tflops": mfma_loop},
         "paper_context": "paper reports end-to-end video latency only (8x H800): PASA 2.19x over dense at Wan 2.1-14B 720p",
     }
     if not args.no_cpu_baseline:

@@ -217,6 +217,15 @@ PASA_API int pasa_l1_distance(const void* a, const void* b, int64_t n, int32_t d
 PASA_API int pasa_budget_schedule(const double* l1, int32_t n_prompts, int32_t n_steps, double rho,
                                   double dense_fraction, double* rho_t);
 
+/*
+ * Measurement aid (not part of the forward, cites nothing): launches `workgroups` workgroups of 256 threads that
+ * each run `iterations` rounds of 8 independent 32x32x16 bf16 MFMAs on register operands, and returns in
+ * *flops (host) the floating-point operations of the launch.  Timed by the caller, it gives the matrix-core rate
+ * the device sustains, which bench.py reports beside the published peak.
+ *   sink   device buffer of at least workgroups * 256 floats (never written in practice)
+ */
+PASA_API int pasa_mfma_probe(int32_t workgroups, int32_t iterations, float* sink, double* flops, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

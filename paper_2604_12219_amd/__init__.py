@@ -19,6 +19,7 @@ from .pasa import (  # noqa: F401
     lib_path,
     load_library,
     mask_words,
+    mfma_probe,
     num_blocks,
     route,
     score_workspace_bytes,

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpasa_hip.so")
-SOURCES = ["pasa_api.hip", "pasa_score.hip", "pasa_route.hip", "pasa_stats.hip", "pasa_attn.hip", "pasa_budget.hip"]
+SOURCES = ["pasa_api.hip", "pasa_score.hip", "pasa_route.hip", "pasa_stats.hip", "pasa_attn.hip", "pasa_budget.hip", "pasa_probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option",

@@ -18,7 +18,7 @@ _lib = None
 EXPORTS = ("pasa_strerror", "pasa_topk_count", "pasa_num_blocks", "pasa_mask_words", "pasa_score_workspace_bytes",
            "pasa_attn_workspace_bytes", "pasa_block_score", "pasa_route", "pasa_route_gumbel", "pasa_kv_stats", "pasa_key_prior", "pasa_sparse_attn_fwd",
            "pasa_sparse_attn_fwd_prepared", "pasa_attn_dense_ref", "pasa_l1_workspace_bytes", "pasa_l1_distance",
-           "pasa_budget_schedule")
+           "pasa_budget_schedule", "pasa_mfma_probe")
 
 
 class PasaError(RuntimeError):
@@ -94,6 +94,8 @@ def load_library() -> ctypes.CDLL:
         L.pasa_route_gumbel.restype = ctypes.c_int
         L.pasa_route_gumbel.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_uint64, ctypes.c_float,
                                  vp, vp, vp]
+        L.pasa_mfma_probe.restype = ctypes.c_int
+        L.pasa_mfma_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.pasa_sparse_attn_fwd.restype = ctypes.c_int
         L.pasa_sparse_attn_fwd.argtypes = [vp, vp, vp, sp, vp, vp, ctypes.c_int32, vp, vp, vp, ctypes.c_size_t, vp]
         L.pasa_sparse_attn_fwd_prepared.restype = ctypes.c_int
@@ -288,3 +290,19 @@ def forward(q, k, v, keep_ratio: float, seed: int, noise_amp: float, block: int 
     route(b["scores"], k_sel, seed, noise_amp, idx=b["idx"], mask=b["mask"])
     sparse_attn_fwd(q, k, v, shape, b["idx"], b["mask"], out=b["out"], ws=b["ws_attn"])
     return b["out"], b["idx"]
+
+
+def mfma_probe(workgroups: int = 4096, iterations: int = 4096, reps: int = 3) -> float:
+    """TFLOP/s of a loop of nothing but bf16 MFMAs on this device (a measurement aid, see pasa.h)"""
+    L = load_library()
+    sink = torch.empty(workgroups * 256, dtype=torch.float32, device="cuda")
+    flops = ctypes.c_double(0.0)
+    _check(L.pasa_mfma_probe(workgroups, iterations, _ptr(sink), ctypes.byref(flops), _stream()), "pasa_mfma_probe")
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        _check(L.pasa_mfma_probe(workgroups, iterations, _ptr(sink), ctypes.byref(flops), _stream()), "pasa_mfma_probe")
+    e1.record()
+    torch.cuda.synchronize()
+    return flops.value * reps / (e0.elapsed_time(e1) * 1e-3) / 1e12
