@@ -122,6 +122,26 @@ __global__ void __launch_bounds__(256, 3) kv_stats_kernel(StatsParams p) {
 #pragma unroll
       for (int r = 0; r < 16; ++r)
         out[(32 * (tin0 + a) + mfma_row(r, h)) * D + 32 * (tout0 + b) + (lane & 31)] = acc[a][b][r];
+
+  // A group of at most 32 blocks is one unit: its matrix is finished here, (scale * Hg)^T as bf16, row = value
+  // column (hg_finish_kernel does the same for groups of several units).  Registers 4g .. 4g + 3 of a lane are four
+  // consecutive key columns of its value column.
+  if (p.group <= 32) {
+    const float f = p.scale / (float)(j_hi - j_lo);
+    uint16_t* hg = p.hg + ((int64_t)bh * p.n_groups + u) * D * D;
+#pragma unroll
+    for (int a = 0; a < TI; ++a)
+#pragma unroll
+      for (int b = 0; b < TI; ++b)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+          bf16x4 v4;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) v4[r] = (__bf16)(acc[a][b][4 * g + r] * f);
+          *reinterpret_cast<bf16x4*>(hg + (int64_t)(32 * (tout0 + b) + (lane & 31)) * D + 32 * (tin0 + a) + 8 * g + 4 * h) = v4;
+        }
+  }
 }
 
 // partial [BH][n_units][d_in][d_out] fp32 -> hg [BH][n_groups][d_out][d_in] bf16 = (scale * Hg)^T
@@ -279,12 +299,13 @@ hipError_t pasa_launch_kv_stats(const StatsParams& p, hipStream_t stream) {
   // few groups (long groups, or one global matrix): spread each matrix over several workgroups
   const int split = (int64_t)p.n_groups * p.bh < 2048 ? p.d * p.d / 8 / 256 : 1;
   dim3 g1(p.n_units, p.bh), g2(p.n_groups, p.bh, split);
+  const bool finish = p.group > 32;  // otherwise a unit is a whole group and kv_stats_kernel writes the matrices itself
   if (p.d == 128) {
     hipLaunchKernelGGL(kv_stats_kernel<128>, g1, dim3(256), 0, stream, p);
-    hipLaunchKernelGGL(hg_finish_kernel<128>, g2, dim3(256), 0, stream, p);
+    if (finish) hipLaunchKernelGGL(hg_finish_kernel<128>, g2, dim3(256), 0, stream, p);
   } else {
     hipLaunchKernelGGL(kv_stats_kernel<64>, g1, dim3(256), 0, stream, p);
-    hipLaunchKernelGGL(hg_finish_kernel<64>, g2, dim3(256), 0, stream, p);
+    if (finish) hipLaunchKernelGGL(hg_finish_kernel<64>, g2, dim3(256), 0, stream, p);
   }
   return hipGetLastError();
 }
