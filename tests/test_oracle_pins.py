@@ -205,6 +205,57 @@ def test_lemma1_bound_holds():
         assert 0 < r <= bound * (1 + 1e-12)
 
 
+def _lemma1_by_hand(q_scaled, k, v, b, G, sel, group_of=None):
+    """Appendix "Error Analysis", Lemma 1, evaluated in numpy straight from K and V (no oracle call):
+    R = sum_{j in U} alpha_j (H_j - Hbar^{(g(j))}),  M = max_{j in U} ||H_j - Hbar^{(g(j))}||_F,  sum_{j in U} alpha_j,
+    alpha_j = exp(q~ . Kbar_j) divided by its largest value over U (a common factor of both sides of the bound)."""
+    n, d = k.shape
+    nb = -(-n // b)
+    blocks = [slice(j * b, min((j + 1) * b, n)) for j in range(nb)]
+    kbar = np.stack([k[s].mean(0) for s in blocks])
+    hj = np.stack([(k[s] - k[s].mean(0)).T @ v[s] for s in blocks])  # Eq.5
+    group_of = group_of or (lambda j: j // G)
+    members = {}
+    for j in range(nb):
+        members.setdefault(j // G, []).append(j)  # Eq.12: consecutive blocks, the last group short
+    hbar = {g: np.mean([hj[j] for j in js], axis=0) for g, js in members.items()}
+    unsel = [j for j in range(nb) if j not in set(int(x) for x in sel)]
+    z = np.array([q_scaled @ kbar[j] for j in unsel])
+    alpha = np.exp(z - z.max())
+    dev = [hj[j] - hbar[group_of(j)] for j in unsel]
+    R = sum(a * dv for a, dv in zip(alpha, dev))
+    return np.sqrt((R * R).sum()), max(np.sqrt((dv * dv).sum()) for dv in dev) * alpha.sum()
+
+
+def test_lemma1_values_against_direct_evaluation():
+    """both outputs of oracle.lemma1 against the definition written out from K and V: four groups, the last one
+    short (3 blocks of 8) and its last block ragged; a wrong group assignment changes the value by far more than
+    the tolerance, so the comparison can fail"""
+    g = rng(70)
+    b, d, G, ksel = 4, 5, 8, 5
+    n = 26 * b + 3  # 27 blocks: groups of 8, 8, 8, 3; tail block of 3 tokens
+    q, k, v = (g.standard_normal((1, n, d)) for _ in range(3))
+    st = oracle.kv_stats(k, v, b, G, want_hj=True)
+    assert st["hg"].shape[1] == 4
+    for t in (0, 50, n - 1):
+        sel = np.sort(g.choice(27, ksel, replace=False)).astype(np.int32)
+        qs = q[0, t] / math.sqrt(d)
+        r, bound = oracle.lemma1(qs, st["kbar"][0], st["hj"][0], st["hg"][0], G, sel)
+        want_r, want_bound = _lemma1_by_hand(qs, k[0], v[0], b, G, sel)
+        np.testing.assert_allclose(r, want_r, rtol=1e-12)
+        np.testing.assert_allclose(bound, want_bound, rtol=1e-12)
+        # sensitivity: the same evaluation with the group boundaries off by one block, or with every block compared
+        # with the next group's mean, is nowhere near
+        wrong_r, _ = _lemma1_by_hand(qs, k[0], v[0], b, G, sel, group_of=lambda j: min((j + 1) // G, 3))
+        assert abs(wrong_r - want_r) > 1e-3 * want_r
+        wrong_r, wrong_bound = _lemma1_by_hand(qs, k[0], v[0], b, G, sel, group_of=lambda j: (j // G + 1) % 4)
+        assert abs(wrong_r - want_r) > 1e-3 * want_r and abs(wrong_bound - want_bound) > 1e-3 * want_bound
+    # with every deviation zero the residual vanishes: one group per block
+    st1 = oracle.kv_stats(k, v, b, 1, want_hj=True)
+    r, bound = oracle.lemma1(q[0, 0] / math.sqrt(d), st1["kbar"][0], st1["hj"][0], st1["hg"][0], 1, np.array([2], np.int32))
+    assert r < 1e-13 and bound < 1e-13
+
+
 # ------------------------------------------------------------------------------------------------
 # the piecewise attention
 # ------------------------------------------------------------------------------------------------
