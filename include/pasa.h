@@ -50,7 +50,8 @@ typedef enum {
   PASA_EUNSUPPORTED = -2, /* d, block or group not supported                                          */
   PASA_EWORKSPACE = -3,   /* workspace smaller than pasa_*_workspace_bytes says                        */
   PASA_EALIGN = -4,       /* pointer not 16-byte aligned / stride not a multiple of 8 elements         */
-  PASA_EHIP = -5          /* the HIP runtime refused a launch                                          */
+  PASA_EHIP = -5,         /* the HIP runtime refused a launch                                          */
+  PASA_ESCRATCH = -6      /* pasa_sparse_attn_fwd_static: the shape needs more than PASA_STATIC_SCRATCH_BYTES  */
 } pasa_status;
 
 typedef struct {
@@ -185,6 +186,24 @@ PASA_API int pasa_sparse_attn_fwd(const void* q, const void* k, const void* v, c
 PASA_API int pasa_sparse_attn_fwd_prepared(const void* q, const void* k, const void* v, const pasa_shape_t* shape,
                                            const int32_t* idx, const uint32_t* mask, int32_t k_sel, void* out,
                                            float* lse, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * pasa_sparse_attn_fwd for callers that cannot allocate device memory or hand over a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and errors as
+ * pasa_sparse_attn_fwd without `ws`: the key/value statistics go to a buffer of PASA_STATIC_SCRATCH_BYTES that is
+ * part of the library's device image (one copy per GPU, held until the process ends).  The call allocates and frees
+ * nothing and calls no allocating routine; its first call on a device looks the buffer's address up once (make
+ * that call outside a graph capture).  shape->kv_slices is ignored (no slicing).
+ *   PASA_ESCRATCH if pasa_attn_workspace_bytes(shape with kv_slices = 1) > PASA_STATIC_SCRATCH_BYTES
+ *   (e.g. the Wan-1.3B 480p shape, 12 heads of 32,760 tokens, needs 22 MiB; 40 heads of 75,600 tokens do not fit).
+ * All calls on one GPU share the buffer: two calls that overlap in time on one GPU (different streams, or
+ * different host threads) race and give wrong results.  Nothing in it has to be cleared between calls (every
+ * part is rewritten before it is read).
+ */
+#define PASA_STATIC_SCRATCH_BYTES (32u << 20)
+PASA_API int pasa_sparse_attn_fwd_static(const void* q, const void* k, const void* v, const pasa_shape_t* shape,
+                                         const int32_t* idx, const uint32_t* mask, int32_t k_sel, void* out,
+                                         float* lse, void* stream);
 
 /*
  * Dense attention, Eq.1: O = softmax(Q K^T * scale) V, same kernels with every block selected.

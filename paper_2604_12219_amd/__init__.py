@@ -24,5 +24,7 @@ from .pasa import (  # noqa: F401
     route,
     score_workspace_bytes,
     sparse_attn_fwd,
+    sparse_attn_fwd_static,
+    STATIC_SCRATCH_BYTES,
     topk_count,
 )

@@ -5,6 +5,15 @@
 
 #include <math.h>
 
+#include <atomic>
+#include <mutex>
+
+// Scratch of pasa_sparse_attn_fwd_static, the entry point that allocates nothing: the attention workspace
+// (statistics tiles, group matrices, unit sums) lives in this array instead of a caller's buffer.  Every GPU the
+// library runs on holds its own copy until the process ends.  In host code the name is only a handle for
+// hipGetSymbolAddress; the device address it yields is kept per device and is what the kernels receive.
+static __device__ __align__(256) unsigned char scratch[PASA_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 constexpr size_t kAlign = 256;
@@ -84,6 +93,30 @@ AttnWorkspace carve_attn(const pasa_shape_t* s) {
   return w;
 }
 
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each device, null until looked up
+std::mutex g_scratch_mutex;
+
+// Device address of the static scratch array on the current device (looked up once per device).
+int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return PASA_EHIP;
+  void* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    ptr = g_scratch_ptr[dev].load(std::memory_order_relaxed);
+    if (!ptr) {
+      if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+        (void)hipGetLastError();
+        return PASA_EHIP;
+      }
+      g_scratch_ptr[dev].store(ptr, std::memory_order_release);
+    }
+  }
+  *out = ptr;
+  return PASA_OK;
+}
+
 }  // namespace
 
 #ifdef PASA_PROFILE_PHASES
@@ -105,6 +138,7 @@ const char* pasa_strerror(int status) {
     case PASA_EWORKSPACE: return "workspace too small";
     case PASA_EALIGN: return "pointer or stride not sufficiently aligned";
     case PASA_EHIP: return "HIP launch failure";
+    case PASA_ESCRATCH: return "problem needs more scratch than the static buffer of the no-allocation entry point holds";
     default: return "unknown status";
   }
 }
@@ -300,6 +334,23 @@ int pasa_sparse_attn_fwd_prepared(const void* q, const void* k, const void* v, c
                                   const int32_t* idx, const uint32_t* mask, int32_t k_sel, void* out, float* lse,
                                   void* ws, size_t ws_bytes, void* stream) {
   return attn_common(q, k, v, shape, idx, mask, k_sel, out, lse, ws, ws_bytes, stream, true, false);
+}
+
+int pasa_sparse_attn_fwd_static(const void* q, const void* k, const void* v, const pasa_shape_t* shape,
+                                const int32_t* idx, const uint32_t* mask, int32_t k_sel, void* out, float* lse,
+                                void* stream) {
+  const int rc = check_shape(shape);
+  if (rc != PASA_OK) return rc;
+  pasa_shape_t s = *shape;
+  s.kv_slices = 1;  // the partial results of key-range slicing do not fit a modest static buffer
+  const size_t need = pasa_attn_workspace_bytes(&s);
+  if (need == 0) return check_group(s.group, num_blocks(&s)) != PASA_OK ? check_group(s.group, num_blocks(&s)) : PASA_EINVAL;
+  if (need > (size_t)PASA_STATIC_SCRATCH_BYTES) return PASA_ESCRATCH;
+  if (!q || !k || !v || !out || !idx || !mask) return PASA_EINVAL;
+  void* ws = nullptr;
+  const int rp = static_scratch(&ws);
+  if (rp != PASA_OK) return rp;
+  return attn_common(q, k, v, &s, idx, mask, k_sel, out, lse, ws, (size_t)PASA_STATIC_SCRATCH_BYTES, stream, true, true);
 }
 
 int pasa_attn_dense_ref(const void* q, const void* k, const void* v, const pasa_shape_t* shape, void* out, float* lse,

@@ -17,7 +17,7 @@ _lib = None
 
 EXPORTS = ("pasa_strerror", "pasa_topk_count", "pasa_num_blocks", "pasa_mask_words", "pasa_score_workspace_bytes",
            "pasa_attn_workspace_bytes", "pasa_block_score", "pasa_route", "pasa_route_gumbel", "pasa_kv_stats", "pasa_key_prior", "pasa_sparse_attn_fwd",
-           "pasa_sparse_attn_fwd_prepared", "pasa_attn_dense_ref", "pasa_l1_workspace_bytes", "pasa_l1_distance",
+           "pasa_sparse_attn_fwd_prepared", "pasa_sparse_attn_fwd_static", "pasa_attn_dense_ref", "pasa_l1_workspace_bytes", "pasa_l1_distance",
            "pasa_budget_schedule", "pasa_mfma_probe")
 
 
@@ -100,6 +100,8 @@ def load_library() -> ctypes.CDLL:
         L.pasa_sparse_attn_fwd.argtypes = [vp, vp, vp, sp, vp, vp, ctypes.c_int32, vp, vp, vp, ctypes.c_size_t, vp]
         L.pasa_sparse_attn_fwd_prepared.restype = ctypes.c_int
         L.pasa_sparse_attn_fwd_prepared.argtypes = L.pasa_sparse_attn_fwd.argtypes
+        L.pasa_sparse_attn_fwd_static.restype = ctypes.c_int
+        L.pasa_sparse_attn_fwd_static.argtypes = [vp, vp, vp, sp, vp, vp, ctypes.c_int32, vp, vp, vp]
         L.pasa_kv_stats.restype = ctypes.c_int
         L.pasa_kv_stats.argtypes = [vp, vp, sp, vp, ctypes.c_size_t, vp]
         L.pasa_key_prior.restype = ctypes.c_int
@@ -252,6 +254,17 @@ def sparse_attn_fwd(q, k, v, shape: Shape, idx, mask, out=None, lse=None, ws=Non
     _check(fn(_ptr(q), _ptr(k), _ptr(v), ctypes.byref(shape.c()), _ptr(idx), _ptr(mask), idx.shape[-1], _ptr(out),
               _ptr(lse), _ptr(ws), ws.numel(), _stream()), "pasa_sparse_attn_fwd")
     return (out, lse) if want_lse else out
+
+
+STATIC_SCRATCH_BYTES = 32 << 20  # PASA_STATIC_SCRATCH_BYTES of pasa.h
+
+
+def sparse_attn_fwd_static(q, k, v, shape: Shape, idx, mask, out, lse=None):
+    """pasa_sparse_attn_fwd_static: the caller passes inputs and outputs only; nothing is allocated, here or in the library"""
+    _check(load_library().pasa_sparse_attn_fwd_static(_ptr(q), _ptr(k), _ptr(v), ctypes.byref(shape.c()), _ptr(idx), _ptr(mask),
+                                                      idx.shape[-1], _ptr(out), _ptr(lse), _stream()),
+           "pasa_sparse_attn_fwd_static")
+    return out
 
 
 def attn_dense_ref(q, k, v, shape: Shape, out=None, lse=None, ws=None, want_lse: bool = False):

@@ -135,7 +135,20 @@ def test_argument_validation_returns_before_any_launch(P):
     assert sparse(_shape(P, kv_slices=12).c()) == EUNSUPPORTED
     assert L.pasa_attn_dense_ref(fake, fake, fake, ctypes.byref(good), None, None, fake, big, None) == EINVAL
     assert L.pasa_kv_stats(None, fake, ctypes.byref(good), fake, big, None) == EINVAL
-    for code in (0, -1, -2, -3, -4, -5, -99):
+    # the entry point that allocates nothing: shapes beyond its static scratch are refused on the host
+    ESCRATCH = -6
+
+    def static(shape, q=fake, idx=fake, k=4, out=ctypes.c_void_p(0x2000)):
+        return L.pasa_sparse_attn_fwd_static(q, fake, fake, ctypes.byref(shape), idx, fake, k, out, None, None)
+
+    wan14b = _shape(P, H=40, n=75_600).c()
+    assert P.attn_workspace_bytes(_shape(P, H=40, n=75_600)) > P.STATIC_SCRATCH_BYTES
+    assert static(wan14b) == ESCRATCH
+    assert P.attn_workspace_bytes(_shape(P, H=12, n=32_760)) <= P.STATIC_SCRATCH_BYTES  # the 480p shape fits
+    assert static(good, q=None) == EINVAL and static(good, idx=None) == EINVAL
+    assert static(_shape(P, group=48).c()) == EUNSUPPORTED and static(_shape(P, d=96).c()) == EUNSUPPORTED
+    assert b"static" in L.pasa_strerror(ESCRATCH)
+    for code in (0, -1, -2, -3, -4, -5, -6, -99):
         assert isinstance(L.pasa_strerror(code), bytes) and len(L.pasa_strerror(code)) > 0
 
 
