@@ -98,12 +98,116 @@ def cpu_baseline(w, q, k, v, k_sel, noise_amp, group, target_seconds=20.0):
                 sample=f"{sample}; {total:.1f} s", seconds=total, seconds_per_head_extrapolated=per_head)
 
 
+def run_budget_schedule(args):
+    """The budget-schedule workload: the Wan-1.3B 480p shape run for 50 denoising steps, keep ratio per step from
+    workloads.budget_schedule_keep_ratio (k from 51 to 205 of 512 blocks), a fresh routing seed and freshly drawn
+    inputs (white-noise amplitude 1.0 -> 0.2) per step.  The inputs of all 50 steps are generated first and stay
+    resident in HBM (15 GB); scores, index lists, bitmaps, workspaces and the output are allocated ONCE, sized for the
+    largest k, and every step runs in them: k is a runtime argument, nothing is recompiled or re-allocated.
+    One bench "step" is one denoising step (one call of the whole hot path); --steps is fixed at the schedule length and
+    --warmup runs that many leading steps of the schedule once, untimed, beforehand."""
+    import torch
+    import paper_2604_12219_amd as P
+    import workloads
+
+    P.load_library()
+    assert torch.cuda.is_available(), "no GPU visible"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = workloads.WORKLOADS["wan1.3b-480p"]
+    n_steps = 50
+    nb, bh = w.n_blocks, w.batch * w.heads
+    keeps = [workloads.budget_schedule_keep_ratio(s, n_steps) for s in range(n_steps)]
+    ks = [P.topk_count(nb, r) for r in keeps]
+    k_max = max(ks)
+    inputs = [workloads.make_workload_qkv(w, device=dev, noise_amplitude=workloads.budget_schedule_noise_amplitude(s, n_steps),
+                                          seed=w.seed + s) for s in range(n_steps)]
+    shape = P.Shape.of(inputs[0][0], block=w.block, group=args.group)
+    scores = torch.empty((bh, nb, nb), dtype=torch.float32, device=dev)
+    idx_buf = torch.empty(bh * nb * k_max, dtype=torch.int32, device=dev)
+    mask = torch.empty((bh, nb, P.mask_words(nb)), dtype=torch.int32, device=dev)
+    ws_score = torch.empty(P.score_workspace_bytes(shape), dtype=torch.uint8, device=dev)
+    ws_attn = torch.empty(P.attn_workspace_bytes(shape), dtype=torch.uint8, device=dev)
+    out = torch.empty_like(inputs[0][0])
+    allocated_before = torch.cuda.memory_allocated()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(n_steps)]
+
+    def step(s, events=None):
+        q, k, v = inputs[s]
+        idx = idx_buf[: bh * nb * ks[s]].view(bh, nb, ks[s])
+        if events: events[0].record()
+        P.block_score(q, k, shape, scores=scores, ws=ws_score)
+        if events: events[1].record()
+        P.route(scores, ks[s], w.seed + s, args.noise_amp, idx=idx, mask=mask)
+        if events: events[2].record()
+        P.kv_stats(k, v, shape, ws=ws_attn)
+        if events: events[3].record()
+        P.sparse_attn_fwd(q, k, v, shape, idx, mask, out=out, ws=ws_attn, prepared=True)
+        if events: events[4].record()
+
+    for s in range(min(args.warmup, n_steps)):
+        step(s)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(n_steps):
+        step(s, ev[s])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    assert torch.cuda.memory_allocated() == allocated_before, "a step allocated device memory"
+    per_step_ms = [e[0].elapsed_time(e[4]) for e in ev]
+    attn_ms = [e[3].elapsed_time(e[4]) for e in ev]
+    stage_ms = [sum(e[i].elapsed_time(e[i + 1]) for e in ev) / n_steps for i in range(4)]
+    fl = [algorithmic_flops(w.batch, w.heads, w.n, w.d, w.block, args.group, k_sel) for k_sel in ks]
+    attn_flops, dense_flops = sum(f["attn"] for f in fl), sum(f["dense"] for f in fl)
+    attn_total_s = sum(attn_ms) * 1e-3
+    attn_tflops = attn_flops / attn_total_s / 1e12
+    dense_ms = None
+    if not args.no_dense:
+        q, k, v = inputs[0]
+        P.attn_dense_ref(q, k, v, shape, out=out, ws=ws_attn)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            P.attn_dense_ref(q, k, v, shape, out=out, ws=ws_attn)
+        e1.record()
+        torch.cuda.synchronize()
+        dense_ms = e0.elapsed_time(e1) / 3
+    result = {
+        "metric": "dense-equivalent TFLOP/s over the 50-step budget schedule (sum of 4*B*H*n^2*d / total time); ms per denoising step in ms_per_step",
+        "value": dense_flops / elapsed / 1e12,
+        "unit": "TFLOP/s (dense-equivalent)",
+        "n_gpus": 1, "steps": n_steps, "warmup": min(args.warmup, n_steps), "ms_per_step": elapsed / n_steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "budget-schedule", "shape": w.name, "B": w.batch, "H": w.heads, "n": w.n, "d": w.d, "block": w.block,
+                   "n_blocks": nb, "group": args.group, "noise_amp": args.noise_amp, "seed": "seed + step",
+                   "keep_ratio": "0.1 + 0.3*exp(-((t-0.3)/0.1)^2), t = step/50", "k_sel_min": min(ks), "k_sel_max": k_max,
+                   "k_sel_mean": sum(ks) / n_steps, "input_noise_amplitude": "1.0 -> 0.2, linear"},
+        "total_ms": elapsed * 1e3,
+        "per_step": {"k_sel": ks, "ms": [round(x, 4) for x in per_step_ms], "attn_ms": [round(x, 4) for x in attn_ms]},
+        "stage_ms_mean": {"block_score": stage_ms[0], "route": stage_ms[1], "kv_stats": stage_ms[2], "sparse_attn": stage_ms[3]},
+        "buffers_allocated_once": True,
+        "dense_ref_ms": dense_ms,
+        "speedup_vs_dense_ref": (dense_ms * n_steps / (elapsed * 1e3)) if dense_ms else None,
+        "roofline": {"kernel": "attn_kernel (sparse: exact tiles + grouped approximation), all 50 launches", "bound": "mfma",
+                     "achieved": attn_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                     "avg_launch_ms": sum(attn_ms) / n_steps, "flops_per_launch": attn_flops / n_steps},
+    }
+    if not args.no_cpu_baseline:
+        q, k, v = inputs[15]  # the step with the largest k
+        result["cpu_baseline"] = cpu_baseline(w, q, k, v, ks[15], args.noise_amp, args.group, args.cpu_seconds)
+        result["cpu_baseline"]["sample"] = "schedule step 15 (k = %d): " % ks[15] + result["cpu_baseline"]["sample"]
+    print(json.dumps(result))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="wan14b-720p")
+    ap.add_argument("--workload", default="wan14b-720p",
+                    help="a name of workloads.WORKLOADS, or budget-schedule (50 denoising steps of the 480p shape with a per-step keep ratio)")
     ap.add_argument("--noise-amp", type=float, default=NOISE_AMP_DEFAULT)
     ap.add_argument("--group", type=int, default=32)
     ap.add_argument("--kv-slices", type=int, default=0, help="key-range slices of the attention kernel (0 = the library's choice)")
@@ -120,6 +224,9 @@ def main():
         print("bench.py: this build runs on ONE GPU only (heads would shard across GPUs with no collective); "
               "--gpus must be 1", file=sys.stderr)
         sys.exit(2)
+
+    if args.workload == "budget-schedule":
+        return run_budget_schedule(args)
 
     import torch
     import paper_2604_12219_amd as P
@@ -217,6 +324,8 @@ def main():
     traffic = MEASURED_TRAFFIC_BYTES.get((w.name, args.group)) if args.kv_slices in (0, 1) and not args.with_prior else None
     # what a loop of nothing but MFMAs reaches on this device right now (the published peak assumes 2.4 GHz)
     mfma_loop = None if args.no_mfma_probe else P.mfma_probe()
+    # ... and with N(0,1)-like operands in the registers: the matrix cores draw more power and the clock drops
+    mfma_loop_data = None if args.no_mfma_probe else P.mfma_probe(random_operands=True)
     result = {
         "metric": "dense-equivalent TFLOP/s of one PASA sparse-attention call (4*B*H*n^2*d / time); ms per call in ms_per_step",
         "value": dense_equiv_tflops,
@@ -249,7 +358,7 @@ def main():
                      "traffic_rate_TBps": (traffic / (attn_ms * 1e-3) / 1e12) if traffic else None,
                      "avg_launch_ms": attn_ms, "flops_per_launch": fl["attn"],
                      "unshared_tile_TBps": tile_bytes / (attn_ms * 1e-3) / 1e12,
-                     "mfma_loop_tflops": mfma_loop},
+                     "mfma_loop_tflops": mfma_loop, "mfma_loop_random_operands_tflops": mfma_loop_data},
         "paper_context": "paper reports end-to-end video latency only (8x H800): PASA 2.19x over dense at Wan 2.1-14B 720p",
     }
     if not args.no_cpu_baseline:

@@ -28,6 +28,13 @@
  *     reported as PASA_EHIP (hipGetLastError after the launch; never a device synchronise).
  *   - Outputs must not alias inputs.  Base pointers must be 16-byte aligned and strides multiples of
  *     8 elements (PASA_EALIGN otherwise).
+ *   - Size limits (PASA_EUNSUPPORTED beyond them): B * H <= 65535; n * stride_n * 2 < 2^32 (byte offsets inside one
+ *     head are 32-bit, i.e. 4 GiB per head and tensor); B * H * ceil(n / 128) < 2^31; at most 262,144 key blocks
+ *     and 65,535 first-order groups per head in pasa_sparse_attn_fwd; at most 4096 key blocks in pasa_route.
+ *   - Device: written for gfx950 (MI355X: 256 compute units in 8 XCDs with an L2 each).  The workgroup-to-tile
+ *     mapping assumes that consecutive workgroup ids go round-robin to 8 XCDs; on a device that deals them out
+ *     differently the results are the same and only cache locality suffers.  Key-range slicing (kv_slices > 1)
+ *     launches two workgroups per compute unit of the current device, as many as can be resident.
  *   - Results are deterministic: no floating-point atomics, fixed reduction order; the same inputs
  *     give the same bits on every call (also with key-range slicing, whose work queue only decides
  *     which workgroup computes an item, not what it computes).
@@ -91,8 +98,9 @@ PASA_API int32_t pasa_mask_words(int32_t n_blocks);
 /* host-only.  Bytes of scratch pasa_block_score needs (pooled Q and K in fp32); 0 on a bad shape. */
 PASA_API size_t pasa_score_workspace_bytes(const pasa_shape_t* shape);
 
-/* host-only.  Bytes of scratch pasa_sparse_attn_fwd and pasa_attn_dense_ref need (key/value block
- * statistics and re-laid-out operands); 0 on a bad shape. */
+/* host-only.  Bytes of scratch pasa_sparse_attn_fwd and pasa_attn_dense_ref need (key/value block statistics,
+ * group matrices, room for a selection bitmap; with kv_slices > 1 also the per-slice partial results:
+ * B*H*kv_slices*n*(d+2)*4 bytes, 12.6 GB at 40 heads of 75,600 tokens with 8 slices); 0 on a bad shape. */
 PASA_API size_t pasa_attn_workspace_bytes(const pasa_shape_t* shape);
 
 /*
@@ -173,9 +181,13 @@ PASA_API int pasa_key_prior(const void* k, const void* v, const pasa_shape_t* sh
  * pasa_sparse_attn_fwd recomputes the key/value statistics on every call (pasa_kv_stats, then the
  * attention kernel).  pasa_sparse_attn_fwd_prepared runs the attention kernel alone and requires
  * that `ws` was filled by pasa_kv_stats for the same k, v and shape and not touched since.
- *   idx    int32 [BH, N_B, k_sel], each row strictly ascending, values in [0, N_B) (not checked)
- *   mask   the bitmap pasa_route wrote for the same idx.  The kernels walk the bitmap; idx is part of
- *          the interface for callers and checkers and must describe the same selection.
+ *   idx    int32 [BH, N_B, k_sel], each row strictly ascending, values in [0, N_B), or NULL if mask is given
+ *   mask   uint32 [BH, N_B, ceil(N_B/32)], the bitmap of the same selection (as pasa_route writes it), or NULL if
+ *          idx is given.  The kernels walk a bitmap: with mask == NULL one is first built from idx in the workspace
+ *          (a caller with index lists of its own needs nothing else); with both given the bitmap is used and idx
+ *          is not read.  Neither is validated here -- entries outside [0, N_B) are ignored when the bitmap is
+ *          built, set bits at or beyond N_B are a caller error -- pasa_check_selection checks a selection,
+ *          including that list and bitmap agree.
  *   out    bf16 [B,H,n,d] (shape strides)
  *   lse    fp32 [BH, n] or NULL: log(Den) including the subtracted maximum
  *   ws     scratch of pasa_attn_workspace_bytes(shape) bytes, 256-byte aligned
@@ -186,6 +198,18 @@ PASA_API int pasa_sparse_attn_fwd(const void* q, const void* k, const void* v, c
 PASA_API int pasa_sparse_attn_fwd_prepared(const void* q, const void* k, const void* v, const pasa_shape_t* shape,
                                            const int32_t* idx, const uint32_t* mask, int32_t k_sel, void* out,
                                            float* lse, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Validation of a selection before it is handed to pasa_sparse_attn_fwd (debugging aid for callers that build
+ * their own lists or bitmaps).  A row (bh, i) is bad if an index lies outside [0, N_B), its list is not strictly
+ * ascending, its bitmap row has a bit set at or beyond N_B or does not have exactly k_sel bits set, or a listed
+ * block's bit is not set (list and bitmap name different blocks).  Either of idx and mask may be NULL; then only
+ * the other is checked.
+ *   idx int32 [BH, N_B, k_sel];  mask uint32 [BH, N_B, ceil(N_B/32)];  n_bad DEVICE int32 (out): number of bad rows.
+ * Two small kernels on `stream`; the count is an integer sum, hence deterministic.
+ */
+PASA_API int pasa_check_selection(const int32_t* idx, const uint32_t* mask, int32_t BH, int32_t n_blocks, int32_t k_sel,
+                                  int32_t* n_bad, void* stream);
 
 /*
  * pasa_sparse_attn_fwd for callers that cannot allocate device memory or hand over a workspace: code under HIP
@@ -241,9 +265,13 @@ PASA_API int pasa_budget_schedule(const double* l1, int32_t n_prompts, int32_t n
  * each run `iterations` rounds of 8 independent 32x32x16 bf16 MFMAs on register operands, and returns in
  * *flops (host) the floating-point operations of the launch.  Timed by the caller, it gives the matrix-core rate
  * the device sustains, which bench.py reports beside the published peak.
+ *   random_operands  0: all chains share one operand pair of a few distinct small values (least power: the device
+ *                    holds close to its nominal clock); nonzero: every chain has its own operands filled with
+ *                    N(0,1)-like values, as activations are (the clock, and the rate, the matrix cores sustain on data)
  *   sink   device buffer of at least workgroups * 256 floats (never written in practice)
  */
-PASA_API int pasa_mfma_probe(int32_t workgroups, int32_t iterations, float* sink, double* flops, void* stream);
+PASA_API int pasa_mfma_probe(int32_t workgroups, int32_t iterations, int32_t random_operands, float* sink, double* flops,
+                             void* stream);
 
 #ifdef __cplusplus
 }

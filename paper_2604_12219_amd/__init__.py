@@ -11,6 +11,7 @@ from .pasa import (  # noqa: F401
     attn_dense_ref,
     attn_workspace_bytes,
     block_score,
+    check_selection,
     budget_schedule,
     forward,
     key_prior,

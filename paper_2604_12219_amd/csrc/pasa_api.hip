@@ -17,9 +17,12 @@ static __device__ __align__(256) unsigned char scratch[PASA_STATIC_SCRATCH_BYTES
 namespace {
 
 constexpr size_t kAlign = 256;
+constexpr int kMaxChunks = 8192;   // chunks of 32 key blocks per head (262,144 key blocks)
+constexpr int kMaxGroups = 65535;  // first-order groups per head
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
 
 int check_shape(const pasa_shape_t* s) {
   if (!s) return PASA_EINVAL;
@@ -47,7 +50,7 @@ int check_group(int group, int nb) {
 float effective_scale(const pasa_shape_t* s) { return s->scale > 0.f ? s->scale : 1.0f / sqrtf((float)s->d); }
 
 struct AttnWorkspace {
-  size_t st, hg, partial, part_o, part_ml, queue, total;
+  size_t st, hg, partial, part_o, part_ml, queue, bitmap, total;
   int n_groups, unit, n_units, n_chunks, n_slices;
 };
 
@@ -80,6 +83,8 @@ AttnWorkspace carve_attn(const pasa_shape_t* s) {
     w.part_ml = off; off = align_up(off + bh * w.n_slices * s->n * 2 * 4);
     w.queue = off; off = align_up(off + 8 * 4);
   }
+  // room for a selection bitmap built from index lists (callers that pass no bitmap of their own)
+  w.bitmap = off; off = align_up(off + bh * nb * (size_t)w.n_chunks * 4);
   if (s->group > 0) {
     const int group = s->group >= nb ? nb : s->group;
     w.n_groups = (nb + group - 1) / group;
@@ -229,10 +234,29 @@ static int check_attn_args(const pasa_shape_t* shape, bool sparse, const void* w
   if (rg != PASA_OK) return rg;
   const int rs = check_slices(s);
   if (rs != PASA_OK) return rs;
+  {  // one workgroup per 128 query rows, counted in 32 bits (also the work items of key-range slicing)
+    const int64_t q_tiles = ((int64_t)s->n + 127) / 128;
+    const int64_t wgs = (int64_t)s->B * s->H * 8 * ((q_tiles + 7) / 8) * (s->kv_slices > 1 ? s->kv_slices / 8 : 1);
+    if (wgs >= ((int64_t)1 << 31)) return PASA_EUNSUPPORTED;
+  }
+  if (sparse) {  // field widths of the approximation pass's tile descriptors (13 bits of chunk, 16 bits of group)
+    const int nb = num_blocks(s);
+    const int group = s->group >= nb ? nb : s->group;
+    if ((nb + 31) / 32 > kMaxChunks) return PASA_EUNSUPPORTED;
+    if (group > 0 && (nb + group - 1) / group > kMaxGroups) return PASA_EUNSUPPORTED;
+  }
   if (!ws) return PASA_EINVAL;
   if (!aligned16(ws)) return PASA_EALIGN;
   if (ws_bytes < pasa_attn_workspace_bytes(s)) return PASA_EWORKSPACE;
   return PASA_OK;
+}
+
+int pasa_check_selection(const int32_t* idx, const uint32_t* mask, int32_t BH, int32_t n_blocks, int32_t k_sel, int32_t* n_bad,
+                         void* stream) {
+  if ((!idx && !mask) || !n_bad || BH < 1 || n_blocks < 1 || k_sel < 1 || k_sel > n_blocks) return PASA_EINVAL;
+  if ((idx && !aligned4(idx)) || (mask && !aligned4(mask)) || !aligned4(n_bad)) return PASA_EALIGN;
+  return pasa_launch_check_selection(idx, mask, (int64_t)BH * n_blocks, n_blocks, k_sel, n_bad, static_cast<hipStream_t>(stream)) ==
+                 hipSuccess ? PASA_OK : PASA_EHIP;
 }
 
 int pasa_kv_stats(const void* k, const void* v, const pasa_shape_t* shape, void* ws, size_t ws_bytes, void* stream) {
@@ -291,7 +315,8 @@ static int attn_common(const void* q, const void* k, const void* v, const pasa_s
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return PASA_EALIGN;
   if (out == q || out == k || out == v) return PASA_EINVAL;
   if (sparse) {
-    if (!idx || !mask || k_sel < 1 || k_sel > nb) return PASA_EINVAL;
+    if ((!idx && !mask) || k_sel < 1 || k_sel > nb) return PASA_EINVAL;
+    if ((idx && !aligned4(idx)) || (mask && !aligned4(mask))) return PASA_EALIGN;
   }
   if (sparse && with_stats) {
     const int rs = pasa_kv_stats(k, v, &s, ws, ws_bytes, stream);
@@ -310,6 +335,12 @@ static int attn_common(const void* q, const void* k, const void* v, const pasa_s
 #endif
   a.n_slices = 1;
   if (sparse) {
+    if (!mask) {  // the caller has index lists only: the bitmap the kernel walks is built from them
+      uint32_t* built = reinterpret_cast<uint32_t*>(base + w.bitmap);
+      if (pasa_launch_mask_from_idx(idx, (int64_t)s.B * s.H * nb, nb, k_sel, built, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return PASA_EHIP;
+      mask = built;
+    }
     a.idx = idx; a.mask = mask; a.k_sel = k_sel; a.mask_words = (nb + 31) / 32;
     a.group = s.group >= nb ? nb : s.group;
     a.st = reinterpret_cast<const uint16_t*>(base + w.st);
@@ -346,7 +377,7 @@ int pasa_sparse_attn_fwd_static(const void* q, const void* k, const void* v, con
   const size_t need = pasa_attn_workspace_bytes(&s);
   if (need == 0) return check_group(s.group, num_blocks(&s)) != PASA_OK ? check_group(s.group, num_blocks(&s)) : PASA_EINVAL;
   if (need > (size_t)PASA_STATIC_SCRATCH_BYTES) return PASA_ESCRATCH;
-  if (!q || !k || !v || !out || !idx || !mask) return PASA_EINVAL;
+  if (!q || !k || !v || !out || (!idx && !mask) || k_sel < 1 || k_sel > num_blocks(&s)) return PASA_EINVAL;
   void* ws = nullptr;
   const int rp = static_scratch(&ws);
   if (rp != PASA_OK) return rp;

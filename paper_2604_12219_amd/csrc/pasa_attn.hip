@@ -319,7 +319,7 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
   constexpr int HPARTS = D / 64;  // 64-row tiles per group matrix
   __shared__ __attribute__((aligned(1024))) char ring[kRing * TILE_BYTES];
 
-  __shared__ int s_item;
+  __shared__ int s_item, s_queue;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int ql = lane & 31, h = lane >> 5;
@@ -353,14 +353,26 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
   for (;;) {
   int bh, qt, slice = 0;
   if constexpr (SLICED) {
-    if (tid == 0) s_item = (int)atomicAdd(p.queue + xcd, 1u);
+    // An item of this XCD's queue; once that is empty, of the next non-empty one, so that every item is computed
+    // whichever XCDs the workgroups of the launch run on (fewer than eight, a masked or partitioned device).
+    if (tid == 0) {
+      int got = -1, from = xcd;
+      for (int t = 0; t < kXcds && got < 0; ++t) {
+        from = (xcd + t) % kXcds;
+        const int x = (int)atomicAdd(p.queue + from, 1u);
+        if (x < p.items_per_xcd) got = x;
+      }
+      s_item = got;
+      s_queue = from;
+    }
     __syncthreads();
     const int item = __builtin_amdgcn_readfirstlane(s_item);
-    __syncthreads();  // everyone has read s_item before it can be written again
-    if (item >= p.items_per_xcd) return;  // queue empty: every wave of the workgroup leaves here
+    const int from = __builtin_amdgcn_readfirstlane(s_queue);
+    __syncthreads();  // everyone has read the item before it can be written again
+    if (item < 0) return;  // all queues empty: every wave of the workgroup leaves here
     const int rounds = p.n_slices / kXcds;
     const int hr = item / p.q_tiles;
-    slice = (hr % rounds) * kXcds + xcd;
+    slice = (hr % rounds) * kXcds + from;
     bh = hr / rounds;
     // start each slice's sweep over the query tiles at the tiles that lie in the slice itself
     qt = (int)((item % p.q_tiles + (int64_t)slice * p.q_tiles / p.n_slices) % p.q_tiles);
@@ -671,7 +683,7 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
     }
   }
   // General loop: the consumer learns what a tile is from a descriptor:
-  //   bits 0-2 kind;  bits 5-12 chunk;  bits 14-25 group
+  //   bits 0-2 kind;  bits 3-15 chunk (at most 8192 chunks);  bits 16-31 group (at most 65535 groups; the host checks both)
   if (approx_on && c_slow < c_hi) {
     enum : uint32_t { kEnd = 0, kStats = 3, kHPart = 4 };
     ring_barrier<NI>(0);  // every wave is done with the ring, and no request is in flight
@@ -684,12 +696,12 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
       const uint16_t* src;
       if (p_part < 0) {
         src = st + (int64_t)p_chunk * 64 * D;
-        desc = kStats | ((uint32_t)p_chunk << 5);
+        desc = kStats | ((uint32_t)p_chunk << 3);
         p_group = (32 * p_chunk) / p.group;
         p_part = 0;
       } else {
         src = hg + ((int64_t)p_group * D + 64 * p_part) * D;
-        desc = kHPart | ((uint32_t)p_chunk << 5) | ((uint32_t)p_group << 14);
+        desc = kHPart | ((uint32_t)p_chunk << 3) | ((uint32_t)p_group << 16);
         if (++p_part == HPARTS) {
           p_part = 0;
           if (++p_group > (min(32 * p_chunk + 32, p.nb) - 1) / p.group) { ++p_chunk; p_part = -1; }
@@ -718,7 +730,7 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
     while (d0 != kEnd) {
       f32x16 a;  // a_j of the chunk
       const uint32_t cur = next_tile();
-      const int chunk = (int)((cur >> 5) & 255u);
+      const int chunk = (int)((cur >> 3) & 8191u);
       approx_chunk_zeroth<D>(slot(it), lo, w, p.c, mask_row[chunk], chunk, p.nb, p.block, p.tail, lane, a);
       ++it;
       float A = 0.f;
@@ -730,7 +742,7 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
 #pragma unroll 1
       while ((d0 & 7u) == kHPart) {
         if constexpr (MULTI) {
-          const int g = (int)((d0 >> 14) & 4095u);
+          const int g = (int)(d0 >> 16);
           A = 0.f;
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
@@ -868,7 +880,12 @@ hipError_t pasa_launch_attn(AttnParams p, bool sparse, int d, hipStream_t stream
   int grid = p.bh * kXcds * p.q_tiles_per_xcd;
   if (p.n_slices > 1) {  // persistent: two workgroups per CU (64 KB of LDS each), work queues per XCD
     p.items_per_xcd = p.bh * (p.n_slices / kXcds) * p.q_tiles;
-    grid = 2 * 256;
+    int dev = 0, cus = 0;  // host queries only: nothing is allocated or synchronised
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) {
+      (void)hipGetLastError();
+      cus = 256;
+    }
+    grid = 2 * cus;
     hipLaunchKernelGGL(reset_queue_kernel, dim3(1), dim3(64), 0, stream, p.queue);
   }
   const hipError_t rc = d == 128 ? launch_d<128>(p, sparse, grid, stream) : launch_d<64>(p, sparse, grid, stream);

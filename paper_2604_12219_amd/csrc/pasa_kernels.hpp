@@ -17,7 +17,7 @@ struct AttnParams {
   unsigned long long* prof;           // experiments only (PASA_PROFILE_PHASES builds): [4 waves][8] cycle sums
   int32_t q_tiles, q_tiles_per_xcd;   // filled in by the launcher
   // sparse path only
-  const int32_t* idx;    // not read by the attention kernel (it walks the bitmap)
+  const int32_t* idx;    // not read by the attention kernel (it walks the bitmap; a caller without one has it built from idx)
   const uint32_t* mask;  // [BH][nb][mask_words]: bit j of a row = key block j is selected
   int32_t k_sel, mask_words;
   const uint16_t* st;    // bf16 [BH][n_chunks][64][d]: rows 0..31 block-mean keys, rows 32..63 block value
@@ -78,3 +78,8 @@ struct RouteParams {
 };
 constexpr int kRouteMaxBlocks = 4096;  // keys of 4 rows are staged in 64 KB of LDS
 hipError_t pasa_launch_route(const RouteParams& p, hipStream_t stream);
+// n_bad[0] = number of rows (of `rows` = BH * nb) whose index list / bitmap row is not a valid selection of k_sel blocks
+hipError_t pasa_launch_check_selection(const int32_t* idx, const uint32_t* mask, int64_t rows, int nb, int k_sel,
+                                       int32_t* n_bad, hipStream_t stream);
+// mask [rows][ceil(nb/32)] from idx [rows][k_sel]
+hipError_t pasa_launch_mask_from_idx(const int32_t* idx, int64_t rows, int nb, int k_sel, uint32_t* mask, hipStream_t stream);

@@ -135,6 +135,62 @@ __global__ void __launch_bounds__(64 * kWavesPerGroup) route_kernel(RouteParams 
   }
 }
 
+// ---- selections handed in by a caller -----------------------------------------------------------------
+// One wavefront per row (head, query block).  A row is bad if an index lies outside [0, nb), the list is not
+// strictly ascending, the bitmap has a bit set at or beyond nb, its population count is not k_sel, or list and
+// bitmap name different blocks.  Either of idx and mask may be null (then only the other is checked).
+__global__ void __launch_bounds__(256) check_selection_kernel(const int32_t* idx, const uint32_t* mask, int64_t rows, int nb,
+                                                              int k_sel, int mask_words, int32_t* n_bad) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  bool bad = false;
+  const uint32_t* mrow = mask ? mask + row * mask_words : nullptr;
+  if (idx) {
+    const int32_t* irow = idx + row * k_sel;
+    for (int e = lane; e < k_sel; e += 64) {
+      const int32_t j = irow[e];
+      if (j < 0 || j >= nb) { bad = true; continue; }
+      if (e > 0 && irow[e - 1] >= j) bad = true;
+      if (mrow && !((mrow[j >> 5] >> (j & 31)) & 1u)) bad = true;
+    }
+  }
+  if (mrow) {
+    int count = 0;
+    for (int wd = lane; wd < mask_words; wd += 64) {
+      const uint32_t x = mrow[wd];
+      count += __popc(x);
+      const int valid = nb - 32 * wd;  // bits of this word that name existing blocks
+      if (valid < 32 && (x >> max(valid, 0)) != 0u) bad = true;
+    }
+#pragma unroll
+    for (int sh = 32; sh >= 1; sh >>= 1) count += __shfl_xor(count, sh);
+    if (count != k_sel) bad = true;  // with the list inside the bitmap and k_sel distinct entries, the two sets are equal
+  }
+  if (__ballot(bad) != 0ull && lane == 0) atomicAdd(n_bad, 1);
+}
+
+__global__ void zero_i32_kernel(int32_t* x) { *x = 0; }
+
+// bitmap rows from ascending index lists: one wavefront per row clears the row's words, then sets its bits
+// (integer atomic OR inside the row: the result does not depend on the order)
+__global__ void __launch_bounds__(256) mask_from_idx_kernel(const int32_t* idx, int64_t rows, int nb, int k_sel, int mask_words,
+                                                            uint32_t* mask) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  uint32_t* mrow = mask + row * mask_words;
+  for (int wd = lane; wd < mask_words; wd += 64) mrow[wd] = 0u;
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  const int32_t* irow = idx + row * k_sel;
+  for (int e = lane; e < k_sel; e += 64) {
+    const int32_t j = irow[e];
+    if (j >= 0 && j < nb) atomicOr(mrow + (j >> 5), 1u << (j & 31));  // out-of-range entries are a caller error; never written
+  }
+}
+
 template <int KPL>
 hipError_t launch_route(const RouteParams& p, hipStream_t stream) {
   const int64_t rows = (int64_t)p.bh * p.nb;
@@ -145,6 +201,20 @@ hipError_t launch_route(const RouteParams& p, hipStream_t stream) {
 }
 
 }  // namespace
+
+hipError_t pasa_launch_check_selection(const int32_t* idx, const uint32_t* mask, int64_t rows, int nb, int k_sel,
+                                       int32_t* n_bad, hipStream_t stream) {
+  hipLaunchKernelGGL(zero_i32_kernel, dim3(1), dim3(1), 0, stream, n_bad);
+  hipLaunchKernelGGL(check_selection_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream, idx, mask, rows, nb, k_sel,
+                     (nb + 31) / 32, n_bad);
+  return hipGetLastError();
+}
+
+hipError_t pasa_launch_mask_from_idx(const int32_t* idx, int64_t rows, int nb, int k_sel, uint32_t* mask, hipStream_t stream) {
+  hipLaunchKernelGGL(mask_from_idx_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream, idx, rows, nb, k_sel,
+                     (nb + 31) / 32, mask);
+  return hipGetLastError();
+}
 
 hipError_t pasa_launch_route(const RouteParams& p, hipStream_t stream) {
   const int kpl = (p.nb + 63) / 64;  // at most kRouteMaxBlocks / 64

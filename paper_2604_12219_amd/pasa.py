@@ -17,7 +17,7 @@ _lib = None
 
 EXPORTS = ("pasa_strerror", "pasa_topk_count", "pasa_num_blocks", "pasa_mask_words", "pasa_score_workspace_bytes",
            "pasa_attn_workspace_bytes", "pasa_block_score", "pasa_route", "pasa_route_gumbel", "pasa_kv_stats", "pasa_key_prior", "pasa_sparse_attn_fwd",
-           "pasa_sparse_attn_fwd_prepared", "pasa_sparse_attn_fwd_static", "pasa_attn_dense_ref", "pasa_l1_workspace_bytes", "pasa_l1_distance",
+           "pasa_sparse_attn_fwd_prepared", "pasa_sparse_attn_fwd_static", "pasa_check_selection", "pasa_attn_dense_ref", "pasa_l1_workspace_bytes", "pasa_l1_distance",
            "pasa_budget_schedule", "pasa_mfma_probe")
 
 
@@ -95,13 +95,15 @@ def load_library() -> ctypes.CDLL:
         L.pasa_route_gumbel.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_uint64, ctypes.c_float,
                                  vp, vp, vp]
         L.pasa_mfma_probe.restype = ctypes.c_int
-        L.pasa_mfma_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, ctypes.POINTER(ctypes.c_double), vp]
+        L.pasa_mfma_probe.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, ctypes.POINTER(ctypes.c_double), vp]
         L.pasa_sparse_attn_fwd.restype = ctypes.c_int
         L.pasa_sparse_attn_fwd.argtypes = [vp, vp, vp, sp, vp, vp, ctypes.c_int32, vp, vp, vp, ctypes.c_size_t, vp]
         L.pasa_sparse_attn_fwd_prepared.restype = ctypes.c_int
         L.pasa_sparse_attn_fwd_prepared.argtypes = L.pasa_sparse_attn_fwd.argtypes
         L.pasa_sparse_attn_fwd_static.restype = ctypes.c_int
         L.pasa_sparse_attn_fwd_static.argtypes = [vp, vp, vp, sp, vp, vp, ctypes.c_int32, vp, vp, vp]
+        L.pasa_check_selection.restype = ctypes.c_int
+        L.pasa_check_selection.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp]
         L.pasa_kv_stats.restype = ctypes.c_int
         L.pasa_kv_stats.argtypes = [vp, vp, sp, vp, ctypes.c_size_t, vp]
         L.pasa_key_prior.restype = ctypes.c_int
@@ -192,6 +194,17 @@ def route(scores, k_sel: int, seed: int, noise_amp: float, idx=None, mask=None, 
     return idx, mask
 
 
+def check_selection(idx, mask, n_blocks: int, k_sel: int, n_bad=None):
+    """number of rows whose index list / bitmap row is not a valid selection of k_sel blocks -> int32 device scalar.
+    idx [BH, N_B, k_sel] or None, mask [BH, N_B, ceil(N_B/32)] or None"""
+    t = idx if idx is not None else mask
+    if n_bad is None:
+        n_bad = torch.empty(1, dtype=torch.int32, device=t.device)
+    _check(load_library().pasa_check_selection(_ptr(idx), _ptr(mask), t.shape[0], n_blocks, k_sel, _ptr(n_bad), _stream()),
+           "pasa_check_selection")
+    return n_bad
+
+
 def kv_stats(k, v, shape: Shape, ws=None):
     """fills (and returns) the attention workspace with the key/value block statistics"""
     L = load_library()
@@ -240,8 +253,9 @@ def budget_schedule(l1, rho: float, dense_fraction: float = 0.2):
 
 
 def sparse_attn_fwd(q, k, v, shape: Shape, idx, mask, out=None, lse=None, ws=None, want_lse: bool = False,
-                    prepared: bool = False):
-    """prepared=True: ``ws`` already holds kv_stats() of the same k, v, shape; run the attention kernel alone"""
+                    prepared: bool = False, k_sel: int | None = None):
+    """prepared=True: ``ws`` already holds kv_stats() of the same k, v, shape; run the attention kernel alone.
+    One of idx and mask may be None (with idx None pass k_sel)."""
     L = load_library()
     if prepared and ws is None:
         raise ValueError("prepared=True needs the workspace kv_stats() filled")
@@ -251,7 +265,8 @@ def sparse_attn_fwd(q, k, v, shape: Shape, idx, mask, out=None, lse=None, ws=Non
         lse = torch.empty((shape.B * shape.H, shape.n), dtype=torch.float32, device=q.device)
     ws = _workspace(attn_workspace_bytes(shape), q.device, ws)
     fn = L.pasa_sparse_attn_fwd_prepared if prepared else L.pasa_sparse_attn_fwd
-    _check(fn(_ptr(q), _ptr(k), _ptr(v), ctypes.byref(shape.c()), _ptr(idx), _ptr(mask), idx.shape[-1], _ptr(out),
+    k_sel = idx.shape[-1] if idx is not None else int(k_sel)
+    _check(fn(_ptr(q), _ptr(k), _ptr(v), ctypes.byref(shape.c()), _ptr(idx), _ptr(mask), k_sel, _ptr(out),
               _ptr(lse), _ptr(ws), ws.numel(), _stream()), "pasa_sparse_attn_fwd")
     return (out, lse) if want_lse else out
 
@@ -305,17 +320,19 @@ def forward(q, k, v, keep_ratio: float, seed: int, noise_amp: float, block: int 
     return b["out"], b["idx"]
 
 
-def mfma_probe(workgroups: int = 4096, iterations: int = 4096, reps: int = 3) -> float:
-    """TFLOP/s of a loop of nothing but bf16 MFMAs on this device (a measurement aid, see pasa.h)"""
+def mfma_probe(workgroups: int = 4096, iterations: int = 4096, reps: int = 3, random_operands: bool = False) -> float:
+    """TFLOP/s of a loop of nothing but bf16 MFMAs on this device (a measurement aid, see pasa.h); with
+    random_operands the operands are N(0,1)-like, which costs power and therefore clock"""
     L = load_library()
     sink = torch.empty(workgroups * 256, dtype=torch.float32, device="cuda")
     flops = ctypes.c_double(0.0)
-    _check(L.pasa_mfma_probe(workgroups, iterations, _ptr(sink), ctypes.byref(flops), _stream()), "pasa_mfma_probe")
+    rnd = 1 if random_operands else 0
+    _check(L.pasa_mfma_probe(workgroups, iterations, rnd, _ptr(sink), ctypes.byref(flops), _stream()), "pasa_mfma_probe")
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(reps):
-        _check(L.pasa_mfma_probe(workgroups, iterations, _ptr(sink), ctypes.byref(flops), _stream()), "pasa_mfma_probe")
+        _check(L.pasa_mfma_probe(workgroups, iterations, rnd, _ptr(sink), ctypes.byref(flops), _stream()), "pasa_mfma_probe")
     e1.record()
     torch.cuda.synchronize()
     return flops.value * reps / (e0.elapsed_time(e1) * 1e-3) / 1e12

@@ -125,14 +125,25 @@ def test_argument_validation_returns_before_any_launch(P):
     def sparse(shape, q=fake, idx=fake, mask=fake, k=4, out=ctypes.c_void_p(0x2000), ws=fake, nbytes=big):
         return L.pasa_sparse_attn_fwd(q, fake, fake, ctypes.byref(shape), idx, mask, k, out, None, ws, nbytes, None)
 
-    assert sparse(good, idx=None) == EINVAL
-    assert sparse(good, mask=None) == EINVAL
+    assert sparse(good, idx=None, mask=None) == EINVAL  # one of the two may be missing, not both
+    assert sparse(good, idx=ctypes.c_void_p(0x1002)) == EALIGN
     assert sparse(good, k=0) == EINVAL and sparse(good, k=129) == EINVAL
     assert sparse(good, out=fake) == EINVAL  # output aliases an input
     assert sparse(good, nbytes=ctypes.c_size_t(0)) == EWORKSPACE
     assert sparse(_shape(P, group=48).c()) == EUNSUPPORTED
     assert sparse(_shape(P, group=-1).c()) == EINVAL
     assert sparse(_shape(P, kv_slices=12).c()) == EUNSUPPORTED
+    # size limits of the approximation pass: more than 65,535 groups (one block per group on a long sequence)
+    assert sparse(_shape(P, n=70_000 * 64, group=1).c()) == EUNSUPPORTED
+    assert P.attn_workspace_bytes(_shape(P, n=70_000 * 64, group=32)) > 0  # 70,000 blocks in groups of 32 are within the limits
+    assert sparse(_shape(P, H=65_535, n=16_000_000).c()) == EUNSUPPORTED  # workgroup count beyond 32 bits
+
+    def check(idx=fake, mask=fake, bh=2, nb=16, k=4, n_bad=fake):
+        return L.pasa_check_selection(idx, mask, bh, nb, k, n_bad, None)
+
+    assert check(idx=None, mask=None) == EINVAL and check(n_bad=None) == EINVAL
+    assert check(k=0) == EINVAL and check(k=17) == EINVAL and check(bh=0) == EINVAL
+    assert check(idx=ctypes.c_void_p(0x1002)) == EALIGN
     assert L.pasa_attn_dense_ref(fake, fake, fake, ctypes.byref(good), None, None, fake, big, None) == EINVAL
     assert L.pasa_kv_stats(None, fake, ctypes.byref(good), fake, big, None) == EINVAL
     # the entry point that allocates nothing: shapes beyond its static scratch are refused on the host
@@ -145,7 +156,7 @@ def test_argument_validation_returns_before_any_launch(P):
     assert P.attn_workspace_bytes(_shape(P, H=40, n=75_600)) > P.STATIC_SCRATCH_BYTES
     assert static(wan14b) == ESCRATCH
     assert P.attn_workspace_bytes(_shape(P, H=12, n=32_760)) <= P.STATIC_SCRATCH_BYTES  # the 480p shape fits
-    assert static(good, q=None) == EINVAL and static(good, idx=None) == EINVAL
+    assert static(good, q=None) == EINVAL and static(good, k=0) == EINVAL and static(good, k=129) == EINVAL
     assert static(_shape(P, group=48).c()) == EUNSUPPORTED and static(_shape(P, d=96).c()) == EUNSUPPORTED
     assert b"static" in L.pasa_strerror(ESCRATCH)
     for code in (0, -1, -2, -3, -4, -5, -6, -99):
