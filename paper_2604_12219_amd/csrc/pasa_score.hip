@@ -50,71 +50,102 @@ __global__ void __launch_bounds__(256) pool_mean_kernel(ScoreParams p) {
 // float s of the h = 0 lanes and float 16 + s of the h = 1 lanes.
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 template <int D>
-__global__ void __launch_bounds__(256) score_gemm_kernel(ScoreParams p) {
+__global__ void __launch_bounds__(256) score_gemm_kernel(ScoreParams p, int runs) {
   constexpr int QF = 32;               // floats per quarter-row
   constexpr int NQ = D / QF;           // quarters
   constexpr int PITCH = QF * 4 + 16;   // bytes per LDS row
   __shared__ __attribute__((aligned(16))) char lds[2][128 * PITCH];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, x = lane & 31, h = lane >> 5;
-  const int bh = blockIdx.z, i0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
+  // Workgroup ids are decoded so that all workgroups of a head run on one XCD (the hardware deals consecutive ids
+  // round-robin to the 8 XCDs): the head's pooled means are then fetched into one L2 instead of eight.
+  const int n_tiles = (p.nb + 63) / 64;
+  const int per_head = runs * n_tiles;
+  // (with fewer than 16 heads that would leave XCDs idle: then ids simply run head by head)
+  const bool by_xcd = p.bh >= 16;
+  const int slot = by_xcd ? blockIdx.x >> 3 : blockIdx.x;
+  const int bh = by_xcd ? (slot / per_head) * 8 + (blockIdx.x & 7) : slot / per_head;
+  if (bh >= p.bh) return;  // padding workgroup: leaves before any barrier
+  const int within = slot % per_head;
+  const int run_id = within % runs, i0 = (within / runs) * 64;
+  // A workgroup owns a strip of 64 score rows and walks a run of 64-column tiles along it: the 256-byte row
+  // segments of consecutive tiles are then written by the same compute unit one after the other, and the cache
+  // lines that straddle two tiles (rows are not a multiple of a line long) are completed in its L2 instead of going
+  // to memory as two partial lines from two different L2s (3x the bytes of the scores themselves when every tile
+  // was a workgroup of its own).
+  const int run = (n_tiles + runs - 1) / runs;
+  const int jt0 = run_id * run, jt1 = min(jt0 + run, n_tiles);
   const float* const qbar = p.qbar + (int64_t)bh * p.nb * D;
   const float* const kbar = p.kbar + (int64_t)bh * p.nb * D;
   // loader role: thread t fetches 16-byte chunk (t & 7) of tile rows (t >> 3) + 32 i, i = 0..3 (rows 0..63 are
   // pooled queries, 64..127 pooled keys); rows past the end are clamped: their products are never stored
-  const float* src[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int r = (tid >> 3) + 32 * i;
-    const float* base = r < 64 ? qbar + (int64_t)min(i0 + r, p.nb - 1) * D : kbar + (int64_t)min(j0 + r - 64, p.nb - 1) * D;
-    src[i] = base + (tid & 7) * 4;
-  }
-  float4 stage[4];
-  auto fetch = [&](int qtr) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) stage[i] = *reinterpret_cast<const float4*>(src[i] + qtr * QF);
-  };
-  auto park = [&](int buf) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      *reinterpret_cast<float4*>(&lds[buf][((tid >> 3) + 32 * i) * PITCH + (tid & 7) * 16]) = stage[i];
-  };
+  // (the staging registers are four named variables and the two roles are macros: with an array captured by a
+  // lambda the compiler kept a copy of the staged values in scratch memory, four times the bytes of the scores)
+  const int ld_row = tid >> 3, ld_col = (tid & 7) * 4;
+  const float* const src0 = qbar + (int64_t)min(i0 + ld_row, p.nb - 1) * D + ld_col;
+  const float* const src1 = qbar + (int64_t)min(i0 + ld_row + 32, p.nb - 1) * D + ld_col;
+  const float* src2 = nullptr;
+  const float* src3 = nullptr;
+  float4 st0, st1, st2, st3;
+#define PASA_SCORE_FETCH(qtr)                                        \
+  do {                                                               \
+    st0 = *reinterpret_cast<const float4*>(src0 + (qtr) * QF);       \
+    st1 = *reinterpret_cast<const float4*>(src1 + (qtr) * QF);       \
+    st2 = *reinterpret_cast<const float4*>(src2 + (qtr) * QF);       \
+    st3 = *reinterpret_cast<const float4*>(src3 + (qtr) * QF);       \
+  } while (0)
+#define PASA_SCORE_PARK(buf)                                                                       \
+  do {                                                                                             \
+    *reinterpret_cast<float4*>(&lds[buf][(ld_row) * PITCH + (tid & 7) * 16]) = st0;                \
+    *reinterpret_cast<float4*>(&lds[buf][(ld_row + 32) * PITCH + (tid & 7) * 16]) = st1;           \
+    *reinterpret_cast<float4*>(&lds[buf][(ld_row + 64) * PITCH + (tid & 7) * 16]) = st2;           \
+    *reinterpret_cast<float4*>(&lds[buf][(ld_row + 96) * PITCH + (tid & 7) * 16]) = st3;           \
+  } while (0)
   // consumer role: wave (wi, wj) multiplies query rows 32 wi + x with key rows 32 wj + x
   const int a_off = (32 * (wave >> 1) + x) * PITCH + h * 64, b_off = (64 + 32 * (wave & 1) + x) * PITCH + h * 64;
-  f32x16 acc = {0};
-  fetch(0);
-  park(0);
-  __syncthreads();
+#pragma unroll 1
+  for (int jt = jt0; jt < jt1; ++jt) {
+    const int j0 = jt * 64;
+    src2 = kbar + (int64_t)min(j0 + ld_row, p.nb - 1) * D + ld_col;
+    src3 = kbar + (int64_t)min(j0 + ld_row + 32, p.nb - 1) * D + ld_col;
+    f32x16 acc = {0};
+    PASA_SCORE_FETCH(0);
+    PASA_SCORE_PARK(0);  // buffer 0 was last read two barriers ago
+    __syncthreads();
 #pragma unroll
-  for (int qtr = 0; qtr < NQ; ++qtr) {
-    if (qtr + 1 < NQ) fetch(qtr + 1);
-    const char* buf = lds[qtr & 1];
-    float4 a[4], b[4];
+    for (int qtr = 0; qtr < NQ; ++qtr) {
+      if (qtr + 1 < NQ) PASA_SCORE_FETCH(qtr + 1);
+      const char* buf = lds[qtr & 1];
+      float4 a[4], b[4];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      a[c] = *reinterpret_cast<const float4*>(buf + a_off + 16 * c);
-      b[c] = *reinterpret_cast<const float4*>(buf + b_off + 16 * c);
+      for (int c = 0; c < 4; ++c) {
+        a[c] = *reinterpret_cast<const float4*>(buf + a_off + 16 * c);
+        b[c] = *reinterpret_cast<const float4*>(buf + b_off + 16 * c);
+      }
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[c].x, b[c].x, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[c].y, b[c].y, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[c].z, b[c].z, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[c].w, b[c].w, acc, 0, 0, 0);
+      }
+      if (qtr + 1 < NQ) {
+        PASA_SCORE_PARK((qtr + 1) & 1);  // the other buffer: its readers finished before the previous barrier
+        __syncthreads();
+      }
     }
+    // result register 4g + r of lane (x, h) is row 8g + 4h + r, column x of the wave's quarter
+    const int j = j0 + 32 * (wave & 1) + x;
+    if (j < p.nb) {
+      const float bias = p.key_bias ? p.key_bias[(int64_t)bh * p.nb + j] : 0.f;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[c].x, b[c].x, acc, 0, 0, 0);
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[c].y, b[c].y, acc, 0, 0, 0);
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[c].z, b[c].z, acc, 0, 0, 0);
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[c].w, b[c].w, acc, 0, 0, 0);
-    }
-    if (qtr + 1 < NQ) {
-      park((qtr + 1) & 1);  // the other buffer: its readers finished before the previous barrier
-      __syncthreads();
+      for (int r = 0; r < 16; ++r) {
+        const int i = i0 + 32 * (wave >> 1) + 8 * (r >> 2) + 4 * h + (r & 3);
+        if (i < p.nb) p.scores[((int64_t)bh * p.nb + i) * p.nb + j] = fmaf(acc[r], p.scale, bias);
+      }
     }
   }
-  // result register 4g + r of lane (x, h) is row 8g + 4h + r, column x of the wave's quarter
-  const int j = j0 + 32 * (wave & 1) + x;
-  if (j >= p.nb) return;
-  const float bias = p.key_bias ? p.key_bias[(int64_t)bh * p.nb + j] : 0.f;
-#pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int i = i0 + 32 * (wave >> 1) + 8 * (r >> 2) + 4 * h + (r & 3);
-    if (i < p.nb) p.scores[((int64_t)bh * p.nb + i) * p.nb + j] = fmaf(acc[r], p.scale, bias);
-  }
+#undef PASA_SCORE_FETCH
+#undef PASA_SCORE_PARK
 }
 
 }  // namespace
@@ -122,13 +153,17 @@ __global__ void __launch_bounds__(256) score_gemm_kernel(ScoreParams p) {
 hipError_t pasa_launch_block_score(const ScoreParams& p, hipStream_t stream) {
   const dim3 gp(p.nb, p.bh, 2);
   const int tiles = (p.nb + 63) / 64;
-  const dim3 gg(tiles, tiles, p.bh);
+  // strips of 64 rows; a strip is cut into runs of column tiles only as far as it takes to fill the device
+  const int64_t strips = (int64_t)tiles * p.bh;
+  int runs = (int)((2048 + strips - 1) / strips);
+  runs = runs < 1 ? 1 : runs > tiles ? tiles : runs;
+  const dim3 gg((unsigned)((p.bh >= 16 ? 8 * ((p.bh + 7) / 8) : p.bh) * runs * tiles));
   if (p.d == 128) {
     hipLaunchKernelGGL(pool_mean_kernel<128>, gp, dim3(256), 0, stream, p);
-    hipLaunchKernelGGL(score_gemm_kernel<128>, gg, dim3(256), 0, stream, p);
+    hipLaunchKernelGGL(score_gemm_kernel<128>, gg, dim3(256), 0, stream, p, runs);
   } else {
     hipLaunchKernelGGL(pool_mean_kernel<64>, gp, dim3(256), 0, stream, p);
-    hipLaunchKernelGGL(score_gemm_kernel<64>, gg, dim3(256), 0, stream, p);
+    hipLaunchKernelGGL(score_gemm_kernel<64>, gg, dim3(256), 0, stream, p, runs);
   }
   return hipGetLastError();
 }

@@ -17,43 +17,41 @@
 
 namespace {
 
-// (three workgroups per CU: 152 registers without spills; the default bound lets the compiler take 220 and leaves two)
-template <int D>
-__global__ void __launch_bounds__(256, 3) kv_stats_kernel(StatsParams p) {
-  constexpr int T = 256;
-  constexpr int TI = D / 64;  // 32x32 result tiles per wave along each of d_in, d_out
-  constexpr int TILE_BYTES = 64 * 2 * D;
-  __shared__ __attribute__((aligned(16))) char smem[2 * TILE_BYTES];
-  __shared__ float kmean_s[D], vsum_s[D];
-  char* const k_lds = smem;
-  char* const v_lds = smem + TILE_BYTES;
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5;
-  const int u = blockIdx.x, bh = blockIdx.y;
+// The sweep both kernels below share.  A workgroup of four waves owns a unit of consecutive key blocks [j_lo, j_hi)
+// of one head and streams their 64-row K and V tiles through LDS (the next tile's global loads are in flight
+// during the MFMAs of the current one).  Wave w accumulates the (d_in, d_out) quarter (w >> 1, w & 1) of
+// sum K^T V in acc[TI][TI] (32x32 tiles, both operands by transposing LDS reads, the contraction runs over tokens).
+// The column sums the rank-one term needs come from the matrix cores as well, as products with an all-ones
+// operand: ksum[a][r] = sum over the block's tokens of K[:, 32 (tin0 + a) + mfma_row(r, h)] (what a lane needs to
+// correct its rows of the accumulator) and vsum[b][*] = sum of V[:, 32 (tout0 + b) + (lane & 31)] (every register
+// the same value).  After the last tile of block j, done(j, len, acc, ksum, vsum) runs with len = valid tokens of
+// the block; the sums restart at zero afterwards, acc is the callback's to reset or keep.  Rows beyond the last
+// token are staged as zeros, so they add nothing anywhere.
+template <int D, typename BlockDone>
+PASA_DEVICE void sweep_unit(const StatsParams& p, int bh, int j_lo, int j_hi, char* k_lds, char* v_lds,
+                            f32x16 (&acc)[D / 64][D / 64], BlockDone&& done) {
+  constexpr int T = 256;
+  constexpr int TI = D / 64;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int64_t head_off = (int64_t)(bh / p.H) * p.stride_b + (int64_t)(bh % p.H) * p.stride_h;
   const uint16_t* const kb = p.k + head_off;
   const uint16_t* const vb = p.v + head_off;
-  const int j_lo = u * p.unit, j_hi = min(j_lo + p.unit, p.nb);
   const int tiles_per_block = p.block / 64;
-
-  f32x16 acc[TI][TI];
-#pragma unroll
-  for (int a = 0; a < TI; ++a)
-#pragma unroll
-    for (int b = 0; b < TI; ++b) acc[a][b] = f32x16{0};
   const int tin0 = (wave >> 1) * TI, tout0 = (wave & 1) * TI;
-
-  // thread c < D sums column c of K, thread D + c column c of V
-  const bool is_k_col = tid < D, is_v_col = (tid >= D) && (tid < 2 * D);
-  const int col = is_k_col ? tid : tid - D;
-  float colsum = 0.f;
+  bf16x8 ones;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
+  f32x16 ksum[TI], vsum[TI];
+#pragma unroll
+  for (int a = 0; a < TI; ++a) ksum[a] = vsum[a] = f32x16{0};
 
   TileStage<D, T> sk, sv;
   const int n_tiles = (j_hi - j_lo) * tiles_per_block;
   auto tile_row0 = [&](int t) { return (j_lo + t / tiles_per_block) * p.block + (t % tiles_per_block) * 64; };
   sk.load(kb, p.stride_n, tile_row0(0), 64, p.n, tid);
   sv.load(vb, p.stride_n, tile_row0(0), 64, p.n, tid);
-
   for (int t = 0; t < n_tiles; ++t) {
     sk.store(k_lds, 64, tid);
     sv.store(v_lds, 64, tid);
@@ -61,14 +59,6 @@ __global__ void __launch_bounds__(256, 3) kv_stats_kernel(StatsParams p) {
     if (t + 1 < n_tiles) {
       sk.load(kb, p.stride_n, tile_row0(t + 1), 64, p.n, tid);
       sv.load(vb, p.stride_n, tile_row0(t + 1), 64, p.n, tid);
-    }
-    if (is_k_col || is_v_col) {
-      const char* src = is_k_col ? k_lds : v_lds;
-#pragma unroll 8
-      for (int r = 0; r < 64; ++r) {
-        const __bf16 x = *reinterpret_cast<const __bf16*>(src + lds_chunk_off<D>(r, col >> 3) + (col & 7) * 2);
-        colsum += (float)x;
-      }
     }
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
@@ -78,40 +68,76 @@ __global__ void __launch_bounds__(256, 3) kv_stats_kernel(StatsParams p) {
 #pragma unroll
       for (int b = 0; b < TI; ++b) bf[b] = col_frag<D>(v_lds, 16 * ks, 32 * (tout0 + b), lane);
 #pragma unroll
-      for (int a = 0; a < TI; ++a)
+      for (int a = 0; a < TI; ++a) {
+        ksum[a] = mfma32(af[a], ones, ksum[a]);
 #pragma unroll
         for (int b = 0; b < TI; ++b) acc[a][b] = mfma32(af[a], bf[b], acc[a][b]);
-    }
-    const bool block_done = (t % tiles_per_block) == tiles_per_block - 1;
-    if (block_done) {
-      const int j = j_lo + t / tiles_per_block;
-      const int len = (j == p.nb - 1) ? p.tail : p.block;
-      if (is_k_col) {
-        const float mean = colsum / (float)len;
-        kmean_s[col] = mean;
-        p.st[(((int64_t)bh * p.n_chunks + (j >> 5)) * 64 + (j & 31)) * D + col] = __builtin_bit_cast(uint16_t, (__bf16)mean);
-      } else if (is_v_col) {
-        vsum_s[col] = colsum;
-        p.st[(((int64_t)bh * p.n_chunks + (j >> 5)) * 64 + 32 + (j & 31)) * D + col] = __builtin_bit_cast(uint16_t, (__bf16)colsum);
       }
-      colsum = 0.f;
+#pragma unroll
+      for (int b = 0; b < TI; ++b) vsum[b] = mfma32(ones, bf[b], vsum[b]);
     }
-    __syncthreads();  // tiles consumed; block statistics visible
-    if (block_done) {
+    if ((t % tiles_per_block) == tiles_per_block - 1) {
+      const int j = j_lo + t / tiles_per_block;
+      done(j, (j == p.nb - 1) ? p.tail : p.block, acc, ksum, vsum);
 #pragma unroll
-      for (int a = 0; a < TI; ++a)
-#pragma unroll
-        for (int b = 0; b < TI; ++b) {
-          const float vcol = vsum_s[32 * (tout0 + b) + (lane & 31)];
-#pragma unroll
-          for (int r = 0; r < 16; ++r) acc[a][b][r] -= kmean_s[32 * (tin0 + a) + mfma_row(r, h)] * vcol;
-        }
+      for (int a = 0; a < TI; ++a) ksum[a] = vsum[a] = f32x16{0};
     }
+    __syncthreads();  // tiles consumed
   }
+}
 
-  if (j_hi == p.nb && (is_k_col || is_v_col)) {  // rows of blocks that do not exist read as zero
+// (two workgroups per CU: the accumulators of the matrix and of the column sums take 128 + 64 registers at d = 128)
+template <int D>
+__global__ void __launch_bounds__(256, 2) kv_stats_kernel(StatsParams p) {
+  constexpr int TI = D / 64;  // 32x32 result tiles per wave along each of d_in, d_out
+  constexpr int TILE_BYTES = 64 * 2 * D;
+  __shared__ __attribute__((aligned(16))) char smem[2 * TILE_BYTES];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5;
+  const int u = blockIdx.x, bh = blockIdx.y;
+  const int j_lo = u * p.unit, j_hi = min(j_lo + p.unit, p.nb);
+  const int tin0 = (wave >> 1) * TI, tout0 = (wave & 1) * TI;
+
+  f32x16 acc[TI][TI];
+#pragma unroll
+  for (int a = 0; a < TI; ++a)
+#pragma unroll
+    for (int b = 0; b < TI; ++b) acc[a][b] = f32x16{0};
+
+  sweep_unit<D>(p, bh, j_lo, j_hi, smem, smem + TILE_BYTES, acc,
+                [&](int j, int len, f32x16 (&acc)[TI][TI], const f32x16 (&ksum)[TI], const f32x16 (&vsum)[TI]) {
+    const float inv_len = 1.0f / (float)len;
+    uint16_t* const strow = p.st + (((int64_t)bh * p.n_chunks + (j >> 5)) * 64 + (j & 31)) * D;
+#pragma unroll
+    for (int a = 0; a < TI; ++a) {
+      // H_j = K_j^T V_j - Kbar_j^T VS_j: the rank-one term leaves the running sum in fp32, before any rounding
+#pragma unroll
+      for (int b = 0; b < TI; ++b)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[a][b][r] -= ksum[a][r] * inv_len * vsum[b][0];
+      // block-mean key: the waves of the first d_out half hold every d_in row between them; lanes 0 and 32 write
+      // their 4 x 4 consecutive rows
+      if ((wave & 1) == 0 && (lane & 31) == 0) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          bf16x4 m4;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) m4[r] = (__bf16)(ksum[a][4 * g + r] * inv_len);
+          *reinterpret_cast<bf16x4*>(strow + 32 * (tin0 + a) + 8 * g + 4 * h) = m4;
+        }
+      }
+    }
+    // block value sum: the waves of the first d_in half, one value column per lane
+    if ((wave >> 1) == 0 && h == 0) {
+#pragma unroll
+      for (int b = 0; b < TI; ++b) strow[32 * D + 32 * (tout0 + b) + lane] = __builtin_bit_cast(uint16_t, (__bf16)vsum[b][0]);
+    }
+  });
+
+  const bool is_col = tid < 2 * D;
+  if (j_hi == p.nb && is_col) {  // rows of blocks that do not exist read as zero
+    const int col = tid % D;
     for (int j = p.nb; j < 32 * p.n_chunks; ++j)
-      p.st[(((int64_t)bh * p.n_chunks + (j >> 5)) * 64 + (is_v_col ? 32 : 0) + (j & 31)) * D + col] = 0;
+      p.st[(((int64_t)bh * p.n_chunks + (j >> 5)) * 64 + (tid >= D ? 32 : 0) + (j & 31)) * D + col] = 0;
   }
 
   float* out = p.partial + ((int64_t)bh * p.n_units + u) * D * D;
@@ -135,7 +161,6 @@ __global__ void __launch_bounds__(256, 3) kv_stats_kernel(StatsParams p) {
       for (int b = 0; b < TI; ++b)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
           bf16x4 v4;
 #pragma unroll
           for (int r = 0; r < 4; ++r) v4[r] = (__bf16)(acc[a][b][4 * g + r] * f);
@@ -170,27 +195,18 @@ __global__ void __launch_bounds__(256) hg_finish_kernel(StatsParams p) {
 }
 
 // Covariance-aware routing prior (Eq.8): beta_j = log(|| H_j - Hg_{g(j)} ||_F + eps) for every key block.
-// Same sweep as kv_stats_kernel -- a workgroup owns a unit of consecutive blocks of one group, K^T V on the
-// matrix cores, rank-one correction in fp32 -- but H_j is formed per block and compared, element by element
-// in fp32, with the group mean, which the workgroup first sums up from the unit sums that kv_stats_kernel
-// left (`partial`).  Nothing but beta is written.
+// The same sweep as kv_stats_kernel, but H_j is formed per block and compared, element by element in fp32, with the
+// group mean, which the workgroup first sums up from the unit sums that kv_stats_kernel left (`partial`).
+// Nothing but beta is written.
 template <int D>
 __global__ void __launch_bounds__(256) key_prior_kernel(StatsParams p, float eps, float* beta) {
-  constexpr int T = 256;
   constexpr int TI = D / 64;
   constexpr int TILE_BYTES = 64 * 2 * D;
   __shared__ __attribute__((aligned(16))) char smem[2 * TILE_BYTES];
-  __shared__ float kmean_s[D], vsum_s[D], red_s[4];
-  char* const k_lds = smem;
-  char* const v_lds = smem + TILE_BYTES;
-
+  __shared__ float red_s[2][4];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, h = lane >> 5;
   const int u = blockIdx.x, bh = blockIdx.y;
-  const int64_t head_off = (int64_t)(bh / p.H) * p.stride_b + (int64_t)(bh % p.H) * p.stride_h;
-  const uint16_t* const kb = p.k + head_off;
-  const uint16_t* const vb = p.v + head_off;
   const int j_lo = u * p.unit, j_hi = min(j_lo + p.unit, p.nb);
-  const int tiles_per_block = p.block / 64;
   const int tin0 = (wave >> 1) * TI, tout0 = (wave & 1) * TI;
 
   // the group this unit belongs to, and its mean: sum of the group's unit sums / blocks in the group
@@ -221,76 +237,31 @@ __global__ void __launch_bounds__(256) key_prior_kernel(StatsParams p, float eps
 #pragma unroll
     for (int b = 0; b < TI; ++b) acc[a][b] = f32x16{0};
 
-  const bool is_k_col = tid < D, is_v_col = (tid >= D) && (tid < 2 * D);
-  const int col = is_k_col ? tid : tid - D;
-  float colsum = 0.f;
-
-  TileStage<D, T> sk, sv;
-  const int n_tiles = (j_hi - j_lo) * tiles_per_block;
-  auto tile_row0 = [&](int t) { return (j_lo + t / tiles_per_block) * p.block + (t % tiles_per_block) * 64; };
-  sk.load(kb, p.stride_n, tile_row0(0), 64, p.n, tid);
-  sv.load(vb, p.stride_n, tile_row0(0), 64, p.n, tid);
-
-  for (int t = 0; t < n_tiles; ++t) {
-    sk.store(k_lds, 64, tid);
-    sv.store(v_lds, 64, tid);
-    __syncthreads();
-    if (t + 1 < n_tiles) {
-      sk.load(kb, p.stride_n, tile_row0(t + 1), 64, p.n, tid);
-      sv.load(vb, p.stride_n, tile_row0(t + 1), 64, p.n, tid);
-    }
-    if (is_k_col || is_v_col) {
-      const char* src = is_k_col ? k_lds : v_lds;
-#pragma unroll 8
-      for (int r = 0; r < 64; ++r) {
-        const __bf16 x = *reinterpret_cast<const __bf16*>(src + lds_chunk_off<D>(r, col >> 3) + (col & 7) * 2);
-        colsum += (float)x;
-      }
-    }
+  int parity = 0;  // red_s is double-buffered: one barrier per block is enough
+  sweep_unit<D>(p, bh, j_lo, j_hi, smem, smem + TILE_BYTES, acc,
+                [&](int j, int len, f32x16 (&acc)[TI][TI], const f32x16 (&ksum)[TI], const f32x16 (&vsum)[TI]) {
+    const float inv_len = 1.0f / (float)len;
+    float ss = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      bf16x8 af[TI], bf[TI];
+    for (int a = 0; a < TI; ++a)
 #pragma unroll
-      for (int a = 0; a < TI; ++a) af[a] = col_frag<D>(k_lds, 16 * ks, 32 * (tin0 + a), lane);
+      for (int b = 0; b < TI; ++b) {
 #pragma unroll
-      for (int b = 0; b < TI; ++b) bf[b] = col_frag<D>(v_lds, 16 * ks, 32 * (tout0 + b), lane);
-#pragma unroll
-      for (int a = 0; a < TI; ++a)
-#pragma unroll
-        for (int b = 0; b < TI; ++b) acc[a][b] = mfma32(af[a], bf[b], acc[a][b]);
-    }
-    const bool block_done = (t % tiles_per_block) == tiles_per_block - 1;
-    const int j = j_lo + t / tiles_per_block;
-    if (block_done) {
-      const int len = (j == p.nb - 1) ? p.tail : p.block;
-      if (is_k_col) kmean_s[col] = colsum / (float)len;
-      else if (is_v_col) vsum_s[col] = colsum;
-      colsum = 0.f;
-    }
-    __syncthreads();  // tiles consumed; block statistics visible
-    if (block_done) {
-      float ss = 0.f;
-#pragma unroll
-      for (int a = 0; a < TI; ++a)
-#pragma unroll
-        for (int b = 0; b < TI; ++b) {
-          const float vcol = vsum_s[32 * (tout0 + b) + (lane & 31)];
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const float hj = acc[a][b][r] - kmean_s[32 * (tin0 + a) + mfma_row(r, h)] * vcol;
-            const float dlt = hj - mean[a][b][r];
-            ss = fmaf(dlt, dlt, ss);
-          }
-          acc[a][b] = f32x16{0};
+        for (int r = 0; r < 16; ++r) {
+          const float hj = acc[a][b][r] - ksum[a][r] * inv_len * vsum[b][0];
+          const float dlt = hj - mean[a][b][r];
+          ss = fmaf(dlt, dlt, ss);
         }
+        acc[a][b] = f32x16{0};
+      }
 #pragma unroll
-      for (int sh = 32; sh >= 1; sh >>= 1) ss += __shfl_xor(ss, sh);
-      if (lane == 0) red_s[wave] = ss;
-      __syncthreads();
-      if (tid == 0) beta[(int64_t)bh * p.nb + j] = logf(sqrtf(red_s[0] + red_s[1] + red_s[2] + red_s[3]) + eps);
-      // red_s, kmean_s and vsum_s are next written after the barrier at the top of the next tile
-    }
-  }
+    for (int sh = 32; sh >= 1; sh >>= 1) ss += __shfl_xor(ss, sh);
+    if (lane == 0) red_s[parity][wave] = ss;
+    __syncthreads();
+    if (tid == 0)
+      beta[(int64_t)bh * p.nb + j] = logf(sqrtf(red_s[parity][0] + red_s[parity][1] + red_s[parity][2] + red_s[parity][3]) + eps);
+    parity ^= 1;  // the other half is next written after the sweep's own barrier and this one
+  });
 }
 
 }  // namespace
