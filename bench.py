@@ -22,10 +22,43 @@ sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 matrix peak
 HBM_PEAK_BYTES_PER_S = 8.0e12   # MI355X HBM3E
-# HBM-side bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# command (scaled by a plain copy of known size; see profiles/attn_kernel_wan14b-720p_hbm_counters.txt).
-# Measured, not computed here: null for workloads without a committed counter run.
-MEASURED_TRAFFIC_BYTES = {("wan14b-720p", 32): 170.1e9 + 0.774e9}
+# HBM-side bytes per launch of the dominant kernel are MEASURED, not computed here: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs of this command, scaled by a plain copy of known size.  The summaries under profiles/ carry one line per
+# measurement, "bench.traffic: workload=<name> group=<g> bytes_per_launch=<float> kernel_sha=<digest> measured=<date>",
+# where the digest names the attention kernel's sources at the time of the run: a figure measured on other sources is
+# not reported (roofline.traffic = null and roofline.traffic_source says why).
+KERNEL_SOURCES = ("pasa_attn.hip", "pasa_mfma_pipes.hpp", "pasa_device.hpp", "pasa_kernels.hpp")
+
+
+def kernel_source_digest():
+    import hashlib
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2604_12219_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload, group):
+    """-> (bytes per launch or None, where the figure comes from / why there is none)"""
+    digest = kernel_source_digest()
+    stale = None
+    pdir = os.path.join(ROOT, "profiles")
+    for fn in sorted(os.listdir(pdir)) if os.path.isdir(pdir) else []:
+        if not fn.endswith(".txt"):
+            continue
+        for line in open(os.path.join(pdir, fn)):
+            if not line.startswith("bench.traffic:"):
+                continue
+            kv = dict(item.split("=", 1) for item in line.split()[1:])
+            if kv.get("workload") != workload or int(kv.get("group", -1)) != group:
+                continue
+            if kv.get("kernel_sha") == digest:
+                return float(kv["bytes_per_launch"]), f"profiles/{fn} (rocprofv3 --pmc FETCH_SIZE x2 + WRITE_SIZE, measured {kv.get('measured')}, kernel sources {digest})"
+            stale = f"profiles/{fn} was measured on other kernel sources ({kv.get('kernel_sha')}, now {digest}): not reported"
+    return None, stale or f"no counter run committed for workload {workload}, group {group}"
+
+
 NOISE_AMP_DEFAULT = 0.125       # logit units: calibrated once on the 480p workload (~15 % of selections change)
 
 
@@ -321,7 +354,7 @@ def main():
                  for i, name in enumerate(("block_score", "route", "kv_stats"))} if not args.with_prior else None
     # bytes of K/V tiles the attention kernel asks for if no tile were reused between query blocks
     tile_bytes = bh * nb * k_sel * 2 * w.block * w.d * 2
-    traffic = MEASURED_TRAFFIC_BYTES.get((w.name, args.group)) if args.kv_slices in (0, 1) and not args.with_prior else None
+    traffic, traffic_source = measured_traffic(w.name, args.group) if args.kv_slices in (0, 1) and not args.with_prior else (None, "not the default path")
     # what a loop of nothing but MFMAs reaches on this device right now (the published peak assumes 2.4 GHz)
     mfma_loop = None if args.no_mfma_probe else P.mfma_probe()
     # ... and with N(0,1)-like operands in the registers: the matrix cores draw more power and the clock drops
@@ -354,7 +387,9 @@ def main():
         "roofline": {"kernel": "attn_kernel (sparse: exact tiles + grouped approximation)", "bound": "mfma",
                      "achieved": attn_tflops, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": attn_tflops / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": traffic,
+                     "traffic": traffic, "traffic_source": traffic_source,
+                     # what the launch is limited by, from the counters: K/V tile reads that miss the L2 and cross the fabric
+                     "limiter": "reads through the fabric (L2 misses of K/V tiles)" if traffic else None,
                      "traffic_rate_TBps": (traffic / (attn_ms * 1e-3) / 1e12) if traffic else None,
                      "avg_launch_ms": attn_ms, "flops_per_launch": fl["attn"],
                      "unshared_tile_TBps": tile_bytes / (attn_ms * 1e-3) / 1e12,

@@ -124,16 +124,7 @@ int static_scratch(void** out) {
 
 }  // namespace
 
-#ifdef PASA_PROFILE_PHASES
-static unsigned long long* g_prof = nullptr;  // experiments only
-#endif
-
 extern "C" {
-
-#ifdef PASA_PROFILE_PHASES
-// experiments only, not part of the library: device buffer of 32 uint64 receiving per-phase cycle sums
-__attribute__((visibility("default"))) void pasa_debug_set_prof(void* dev_buf) { g_prof = static_cast<unsigned long long*>(dev_buf); }
-#endif
 
 const char* pasa_strerror(int status) {
   switch (status) {
@@ -330,9 +321,6 @@ static int attn_common(const void* q, const void* k, const void* v, const pasa_s
   a.stride_b = s.stride_b; a.stride_h = s.stride_h; a.stride_n = s.stride_n;
   a.bh = s.B * s.H; a.H = s.H; a.n = s.n; a.nb = nb; a.block = s.block; a.tail = s.n - (nb - 1) * s.block;
   a.scale = effective_scale(&s);
-#ifdef PASA_PROFILE_PHASES
-  a.prof = g_prof;
-#endif
   a.n_slices = 1;
   if (sparse) {
     if (!mask) {  // the caller has index lists only: the bitmap the kernel walks is built from them

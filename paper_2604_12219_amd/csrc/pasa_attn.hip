@@ -46,12 +46,6 @@ constexpr int kXcds = 8;    // accelerator complex dies of an MI355X, each with 
 constexpr int kWaves = 4;   // waves per workgroup
 constexpr int kRing = 4;    // LDS tile buffers
 constexpr int kNoBlock = 0x7fffffff;
-#ifdef PASA_PROFILE_PHASES
-constexpr bool kProfile = true;      // per-phase cycle counts into AttnParams::prof
-#else
-constexpr bool kProfile = false;
-#endif
-PASA_DEVICE uint32_t clock32() { return (uint32_t)__builtin_amdgcn_s_memtime(); }
 
 typedef __attribute__((address_space(4))) const int32_t const_i32;
 typedef __attribute__((address_space(4))) const uint32_t const_u32;
@@ -449,8 +443,6 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
   };
   auto request = [&](const uint16_t* base, int r0, int sl) { TileDma<D>::request(tile_ptr(base, r0), x_kv, slot_wave(sl)); };
 
-  uint32_t prof[8] = {0, 0, 0, 0, 0, 0, 0, 0};  // cycles: part 1 barrier, logits+softmax, PV; part 2; steps part 1, part 2; approximation; item
-  const uint32_t t_item = kProfile ? clock32() : 0u;
 
   // ---------------- exact attention, part 1: tiles that all four waves need ----------------
   // (every tile of the dense path; the blocks of a 128-token query block; with two 64-token query
@@ -489,16 +481,13 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
     // order, so a tile that reaches beyond the last token can only be among the last ones.)
 #pragma unroll 1
     while (r_cur >= 0 && r_cur + 64 <= n) {
-      const uint32_t t0 = kProfile ? clock32() : 0u;
       ring_barrier<NI>(0);  // the pair has landed; every wave is done with the previous pair
-      const uint32_t t1 = kProfile ? clock32() : 0u;
       const int r_nxt = plan();
       // the next pair is requested into the other two slots (after the last pair: once more the same, unused)
       const int r_req = r_nxt >= 0 ? r_nxt : r_cur;
       const uint32_t k_tile = slot(2 * pair), v_tile = slot(2 * pair + 1);
       pipes::fused_step(k_tile + lo.k, v_tile + lo.v[0], v_tile + lo.v[1], w.qf, w.o, w.m, w.l, p.c, tile_ptr(kb, r_req),
                         tile_ptr(vb, r_req), x_kv, slot_wave(2 * pair + 2), slot_wave(2 * pair + 3));
-      if (kProfile) { prof[0] += t1 - t0; prof[1] += clock32() - t1; prof[4] += 1; }
       r_cur = r_nxt;
       ++pair;
     }
@@ -532,7 +521,6 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
     only_a.init(mask_a, mask_b, c_lo, c_hi, first_a, first_b);
     only_b.init(mask_a, mask_b, c_lo, c_hi, first_a, first_b);
     int a_blk = only_a.next(lane), b_blk = only_b.next(lane);
-    const uint32_t t0 = kProfile ? clock32() : 0u;
     if (a_blk != kNoBlock || b_blk != kNoBlock) {
       ring_barrier<NI>(0);  // every wave is done with the ring
       request(kb, (a_blk != kNoBlock ? a_blk : b_blk) * 64, 0);
@@ -556,7 +544,6 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
                               x_kv, slot_wave(0), slot_wave(2));
         a_blk = a_nxt;
         b_blk = b_nxt;
-        if (kProfile) prof[5] += 1;
       }
 #pragma unroll 1
       while (a_blk != kNoBlock || b_blk != kNoBlock) {
@@ -585,17 +572,14 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
                               tile_ptr(kb, b_rq2 * 64), x_kv, slot_wave(0), slot_wave(2));
         a_blk = a_nxt;
         b_blk = b_nxt;
-        if (kProfile) prof[5] += 1;
       }
     }
-    if (kProfile) prof[3] += clock32() - t0;
   }
 
   // ---------------- grouped approximation of the unselected blocks ----------------
   // Per chunk of 32 key blocks: its statistics tile, then for every group it intersects the HPARTS
   // tiles of the group matrix.  The tiles stream through the ring three ahead of their use, one
   // barrier per tile.
-  const uint32_t t_approx = kProfile ? clock32() : 0u;
   uint32_t x_ws[NI];  // lane offsets of the loads of a workspace tile (rows of D elements)
   dma.offsets(2 * D, 64, x_ws);
   int c_slow = c_lo;  // first chunk left to the general loop below
@@ -761,12 +745,6 @@ __global__ void __launch_bounds__(kWaves * 64, 2) attn_kernel(AttnParams p) {
         }
       }
     }
-  }
-  if (kProfile && p.prof && lane == 0) {
-    const uint32_t t_end = clock32();
-    prof[6] = t_end - t_approx;
-    prof[7] = t_end - t_item;
-    for (int x = 0; x < 8; ++x) atomicAdd(p.prof + wave * 8 + x, (unsigned long long)prof[x]);
   }
 
   // ---- epilogue ----

@@ -14,7 +14,6 @@ struct AttnParams {
   int64_t stride_b, stride_h, stride_n;
   int32_t bh, H, n, nb, block, tail;  // tail = valid tokens of the last block
   float scale, c;                     // c = scale * log2(e), filled in by the launcher
-  unsigned long long* prof;           // experiments only (PASA_PROFILE_PHASES builds): [4 waves][8] cycle sums
   int32_t q_tiles, q_tiles_per_xcd;   // filled in by the launcher
   // sparse path only
   const int32_t* idx;    // not read by the attention kernel (it walks the bitmap; a caller without one has it built from idx)

@@ -45,7 +45,6 @@ __global__ void __launch_bounds__(64 * kWavesPerGroup) route_kernel(RouteParams 
   extern __shared__ __attribute__((aligned(16))) uint32_t keys_all[];  // [kWavesPerGroup][64 * KPL]
   static_assert(KPL % 4 == 0, "a lane writes whole quads of keys");
   constexpr int NB_PAD = 64 * KPL;
-  constexpr int CNT_BITS = KPL < 8 ? 3 : KPL < 16 ? 4 : KPL < 32 ? 5 : KPL < 64 ? 6 : 7;  // a lane's count is at most KPL
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t row = (int64_t)blockIdx.x * kWavesPerGroup + wave;
   if (row >= (int64_t)p.bh * p.nb) return;  // whole wave leaves; no workgroup barrier is used below
@@ -88,14 +87,12 @@ __global__ void __launch_bounds__(64 * kWavesPerGroup) route_kernel(RouteParams 
 #pragma unroll
   for (int t = 0; t < KPL; ++t) key[t] = keys[lane + 64 * t];
 
-  // wave-wide number of keys that satisfy a predicate: per-lane count, then one ballot per bit of the count
+  // wave-wide number of keys that satisfy a predicate: one compare per key on the vector unit, its lane mask counted
+  // and summed on the scalar unit (which runs beside the vector unit)
   auto wave_count = [&](auto pred) -> int {
-    uint32_t c = 0u;
-#pragma unroll
-    for (int t = 0; t < KPL; ++t) c += pred(key[t]) ? 1u : 0u;
     int total = 0;
 #pragma unroll
-    for (int b = 0; b < CNT_BITS; ++b) total += (int)__popcll(__ballot((c >> b) & 1u)) << b;
+    for (int t = 0; t < KPL; ++t) total += (int)__popcll(__ballot(pred(key[t])));
     return total;
   };
 
