@@ -60,8 +60,8 @@ struct ScoreParams {
   int32_t bh, H, n, nb, block, d;
   float scale;
   const float* key_bias;  // nullable [BH][nb]
-  float* qbar;            // scratch fp32 [BH][nb][d]
-  float* kbar;            // scratch fp32 [BH][nb][d]
+  float* qbar;            // scratch [BH][nb][d] x 4 bytes: block means as split bf16 pairs, per 32 elements 32 x hi then 32 x lo
+  float* kbar;            // the same for the keys
   float* scores;          // out fp32 [BH][nb][nb]
 };
 hipError_t pasa_launch_block_score(const ScoreParams& p, hipStream_t stream);

@@ -33,25 +33,33 @@ __global__ void __launch_bounds__(256) pool_mean_kernel(ScoreParams p) {
     float s = 0.f;
 #pragma unroll
     for (int rr = 0; rr < RPP; ++rr) s += part[rr][tid];
-    float* dst = (which ? p.kbar : p.qbar) + ((int64_t)bh * p.nb + j) * D;
-    dst[tid] = s / (float)len;
+    // The mean leaves as two bf16 numbers, hi = bf16(mean) and lo = bf16(mean - hi) (together 16 significant bits),
+    // so that the score kernel can multiply on the bf16 matrix cores.  Row layout: per quarter of 32 elements one
+    // 128-byte line, 32 x hi then 32 x lo.
+    const float mean = s / (float)len;
+    const __bf16 hi = (__bf16)mean;
+    const __bf16 lo = (__bf16)(mean - (float)hi);
+    uint16_t* dst = reinterpret_cast<uint16_t*>((which ? p.kbar : p.qbar) + ((int64_t)bh * p.nb + j) * D);
+    dst[(tid >> 5) * 64 + (tid & 31)] = __builtin_bit_cast(uint16_t, hi);
+    dst[(tid >> 5) * 64 + 32 + (tid & 31)] = __builtin_bit_cast(uint16_t, lo);
   }
 }
 
-// scores: a workgroup of four waves computes a 64x64 tile, each wave a 32x32 quarter of it, with the fp32
-// MFMA (32x32x2: A is 32 rows x 2, B is 2 x 32 columns, one float of each per lane).  The pooled means are
-// row-major, and an MFMA operand wants one ROW per lane, which as a global load would touch 64 cache lines
-// per instruction.  So the contraction runs in quarters of 32 floats: a quarter of a row is exactly one
-// 128-byte line, the workgroup fetches the quarters of its 64 + 64 rows with fully coalesced 16-byte loads
-// (eight lanes per line), parks them in LDS (rows padded to 144 bytes: conflict-free 16-byte reads down a
-// column of rows), and every lane reads its operands from there.  Two LDS buffers: the loads of the next
-// quarter are in flight during the MFMAs of the current one.  The contraction order is free as long as both
-// operands agree: in a quarter, lane (x, h) holds floats [16h, 16h + 16) of its row, and step s multiplies
-// float s of the h = 0 lanes and float 16 + s of the h = 1 lanes.
+// scores: a workgroup of four waves computes 64x64 tiles, each wave a 32x32 quarter of a tile, on the bf16 matrix
+// cores: with q = qh + ql and k = kh + kl (the split pooled means), q.k = qh.kh + qh.kl + ql.kh up to 2^-16 relative,
+// accumulated in fp32 -- three bf16 MFMAs (32x32x16) instead of eight fp32 ones (32x32x2) per 16 elements of the
+// contraction, five times less matrix time.  The pooled means are row-major, and an MFMA operand wants one ROW per
+// lane, which as a global load would touch 64 cache lines per instruction.  So the contraction runs in quarters of
+// 32 elements: a quarter of a row (hi and lo) is exactly one 128-byte line, the workgroup fetches the quarters of
+// its 64 + 64 rows with fully coalesced 16-byte loads (eight lanes per line), parks them in LDS (rows padded to 144
+// bytes: conflict-free 16-byte reads down a column of rows), and every lane reads its operands from there.  Two LDS
+// buffers: the loads of the next quarter are in flight during the MFMAs of the current one.  In a quarter, lane
+// (x, h) holds elements [8h + 16m, 8h + 16m + 8) of its row for the MFMAs m = 0, 1.
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 template <int D>
 __global__ void __launch_bounds__(256) score_gemm_kernel(ScoreParams p, int runs) {
-  constexpr int QF = 32;               // floats per quarter-row
+  constexpr int QF = 32;               // elements per quarter-row (stored as 32 bf16 hi + 32 bf16 lo = 32 floats' worth of bytes)
   constexpr int NQ = D / QF;           // quarters
   constexpr int PITCH = QF * 4 + 16;   // bytes per LDS row
   __shared__ __attribute__((aligned(16))) char lds[2][128 * PITCH];
@@ -101,7 +109,7 @@ __global__ void __launch_bounds__(256) score_gemm_kernel(ScoreParams p, int runs
     *reinterpret_cast<float4*>(&lds[buf][(ld_row + 96) * PITCH + (tid & 7) * 16]) = st3;           \
   } while (0)
   // consumer role: wave (wi, wj) multiplies query rows 32 wi + x with key rows 32 wj + x
-  const int a_off = (32 * (wave >> 1) + x) * PITCH + h * 64, b_off = (64 + 32 * (wave & 1) + x) * PITCH + h * 64;
+  const int a_off = (32 * (wave >> 1) + x) * PITCH + h * 16, b_off = (64 + 32 * (wave & 1) + x) * PITCH + h * 16;
 #pragma unroll 1
   for (int jt = jt0; jt < jt1; ++jt) {
     const int j0 = jt * 64;
@@ -115,18 +123,18 @@ __global__ void __launch_bounds__(256) score_gemm_kernel(ScoreParams p, int runs
     for (int qtr = 0; qtr < NQ; ++qtr) {
       if (qtr + 1 < NQ) PASA_SCORE_FETCH(qtr + 1);
       const char* buf = lds[qtr & 1];
-      float4 a[4], b[4];
+      // operand fragments of 8 bf16: [m] hi, [2 + m] lo of elements 8h + 16m .. + 8
+      bf16x8 a[4], b[4];
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        a[c] = *reinterpret_cast<const float4*>(buf + a_off + 16 * c);
-        b[c] = *reinterpret_cast<const float4*>(buf + b_off + 16 * c);
+        a[c] = *reinterpret_cast<const bf16x8*>(buf + a_off + 64 * (c >> 1) + 32 * (c & 1));
+        b[c] = *reinterpret_cast<const bf16x8*>(buf + b_off + 64 * (c >> 1) + 32 * (c & 1));
       }
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[c].x, b[c].x, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[c].y, b[c].y, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[c].z, b[c].z, acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[c].w, b[c].w, acc, 0, 0, 0);
+      for (int m = 0; m < 2; ++m) {
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2 + m], b[m], acc, 0, 0, 0);  // ql kh  (small terms first)
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[m], b[2 + m], acc, 0, 0, 0);  // qh kl
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[m], b[m], acc, 0, 0, 0);      // qh kh
       }
       if (qtr + 1 < NQ) {
         PASA_SCORE_PARK((qtr + 1) & 1);  // the other buffer: its readers finished before the previous barrier
