@@ -88,7 +88,10 @@ AttnWorkspace carve_attn(const pasa_shape_t* s) {
   if (s->group > 0) {
     const int group = s->group >= nb ? nb : s->group;
     w.n_groups = (nb + group - 1) / group;
+    // Blocks summed by one workgroup of the statistics kernel: a whole group, at most 32 blocks -- fewer (a power of
+    // two that divides the group) while that leaves the device short of workgroups, at the price of more unit sums.
     w.unit = group < 32 ? group : 32;
+    while (w.unit > 8 && (int64_t)bh * ((nb + w.unit - 1) / w.unit) < 1024) w.unit /= 2;
     w.n_units = (nb + w.unit - 1) / w.unit;
     w.st = off; off = align_up(off + bh * w.n_chunks * 64 * s->d * 2);
     w.hg = off; off = align_up(off + bh * w.n_groups * s->d * s->d * 2);

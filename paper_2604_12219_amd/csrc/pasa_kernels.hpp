@@ -41,7 +41,7 @@ struct StatsParams {
   int32_t bh, H, n, nb, block, tail, d;
   int32_t group;     // > 0
   int32_t n_groups;  // ceil(nb / group)
-  int32_t unit;      // blocks summed by one workgroup: min(group, 32)
+  int32_t unit;      // blocks summed by one workgroup: a power of two that divides the group, at most 32
   int32_t n_units;   // units per head
   float scale;
   int32_t n_chunks;  // ceil(nb / 32)

@@ -149,10 +149,10 @@ __global__ void __launch_bounds__(256, 2) kv_stats_kernel(StatsParams p) {
       for (int r = 0; r < 16; ++r)
         out[(32 * (tin0 + a) + mfma_row(r, h)) * D + 32 * (tout0 + b) + (lane & 31)] = acc[a][b][r];
 
-  // A group of at most 32 blocks is one unit: its matrix is finished here, (scale * Hg)^T as bf16, row = value
+  // A group that is one unit: its matrix is finished here, (scale * Hg)^T as bf16, row = value
   // column (hg_finish_kernel does the same for groups of several units).  Registers 4g .. 4g + 3 of a lane are four
   // consecutive key columns of its value column.
-  if (p.group <= 32) {
+  if (p.unit == p.group) {
     const float f = p.scale / (float)(j_hi - j_lo);
     uint16_t* hg = p.hg + ((int64_t)bh * p.n_groups + u) * D * D;
 #pragma unroll
@@ -173,8 +173,7 @@ __global__ void __launch_bounds__(256, 2) kv_stats_kernel(StatsParams p) {
 template <int D>
 __global__ void __launch_bounds__(256) hg_finish_kernel(StatsParams p) {
   const int g = blockIdx.x, bh = blockIdx.y;
-  int upg = 1;  // units per group
-  if (p.group > 32) upg = (p.group >= p.nb) ? p.n_units : p.group / 32;
+  const int upg = (p.group >= p.nb) ? p.n_units : p.group / p.unit;  // units per group
   const int u_lo = g * upg, u_hi = min(u_lo + upg, p.n_units);
   const int blocks_in_group = min((g + 1) * p.group, p.nb) - g * p.group;
   const float f = p.scale / (float)blocks_in_group;
@@ -211,8 +210,7 @@ __global__ void __launch_bounds__(256) key_prior_kernel(StatsParams p, float eps
 
   // the group this unit belongs to, and its mean: sum of the group's unit sums / blocks in the group
   const int g = j_lo / p.group;
-  int upg = 1;  // units per group
-  if (p.group > 32) upg = (p.group >= p.nb) ? p.n_units : p.group / 32;
+  const int upg = (p.group >= p.nb) ? p.n_units : p.group / p.unit;  // units per group
   const int u_lo = g * upg, u_hi = min(u_lo + upg, p.n_units);
   const float inv_blocks = 1.0f / (float)(min((g + 1) * p.group, p.nb) - g * p.group);
   f32x16 mean[TI][TI];
@@ -270,7 +268,7 @@ hipError_t pasa_launch_kv_stats(const StatsParams& p, hipStream_t stream) {
   // few groups (long groups, or one global matrix): spread each matrix over several workgroups
   const int split = (int64_t)p.n_groups * p.bh < 2048 ? p.d * p.d / 8 / 256 : 1;
   dim3 g1(p.n_units, p.bh), g2(p.n_groups, p.bh, split);
-  const bool finish = p.group > 32;  // otherwise a unit is a whole group and kv_stats_kernel writes the matrices itself
+  const bool finish = p.unit != p.group;  // otherwise a unit is a whole group and kv_stats_kernel writes the matrices itself
   if (p.d == 128) {
     hipLaunchKernelGGL(kv_stats_kernel<128>, g1, dim3(256), 0, stream, p);
     if (finish) hipLaunchKernelGGL(hg_finish_kernel<128>, g2, dim3(256), 0, stream, p);

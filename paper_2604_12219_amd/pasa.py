@@ -271,7 +271,7 @@ def sparse_attn_fwd(q, k, v, shape: Shape, idx, mask, out=None, lse=None, ws=Non
     return (out, lse) if want_lse else out
 
 
-STATIC_SCRATCH_BYTES = 32 << 20  # PASA_STATIC_SCRATCH_BYTES of pasa.h
+STATIC_SCRATCH_BYTES = 64 << 20  # PASA_STATIC_SCRATCH_BYTES of pasa.h
 
 
 def sparse_attn_fwd_static(q, k, v, shape: Shape, idx, mask, out, lse=None):
