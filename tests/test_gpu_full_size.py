@@ -84,12 +84,13 @@ def test_full_size_dense_reference_sampled_against_oracle(P):
     np.testing.assert_allclose(lse.cpu().numpy()[:, rows], ref_lse, atol=2e-2)
 
 
-def test_whole_head_of_the_headline_workload_against_oracle(P):
-    """Every query block of one head in the middle of the launch at the Wan-14B 720p shape, all 40 heads launched as
-    bench.py launches them: covers every slot of the kernel's workgroup-id decode for that head and the ragged last
-    query tile.  Routing bit for bit, output and lse row by row."""
-    w = workloads.WORKLOADS["wan14b-720p"]
-    head = 20
+@pytest.mark.parametrize("name,head", [("wan14b-720p", 20), ("long-video", 33), ("wan1.3b-480p", 7)])
+def test_whole_head_of_a_full_size_workload_against_oracle(P, name, head):
+    """Every query block of one head in the middle of the launch, all heads launched as bench.py launches them: covers
+    every slot of the kernel's workgroup-id decode for that head and the ragged last query tile (two 64-token query
+    blocks per workgroup at the 14B and 480p shapes, one 128-token block at the long-video shape).  Routing bit for
+    bit, output and lse row by row."""
+    w = workloads.WORKLOADS[name]
     q, k, v = workloads.make_workload_qkv(w, device="cuda")
     shape = P.Shape.of(q, block=w.block, group=32)
     nb = P.num_blocks(shape)
@@ -104,7 +105,7 @@ def test_whole_head_of_the_headline_workload_against_oracle(P):
     np.testing.assert_array_equal(idx[head:head + 1].cpu().numpy(), want_idx)
     res = oracle.pasa_attention(qh, kh, vh, want_idx, w.block, group=32, return_all=True)
     got = to_f64(out[:, head:head + 1])
-    assert_close(got, res["o"], what=f"wan14b-720p whole head {head}")
+    assert_close(got, res["o"], what=f"{name} whole head {head}")
     np.testing.assert_allclose(lse[head].cpu().numpy(), res["lse"][0], atol=2e-2)
     # no query tile is off by more than the others: the per-tile errors stay within the same bounds
     err = np.abs(got[0] - res["o"][0])

@@ -374,3 +374,34 @@ def test_forward_on_a_side_stream_and_in_a_graph_replays_identically(P):
         torch.cuda.synchronize()
         assert torch.equal(out, eager)
         (out.float().sum()).item()  # eager work between the replays
+
+
+# ------------------------------------------------------------------------------------------------
+# the method-variant tables (group sizes, routing noise, selection-count histogram) on the tiny workload
+# ------------------------------------------------------------------------------------------------
+def _table_rows(text):
+    rows = [[c.strip() for c in line.strip().strip("|").split("|")] for line in text.splitlines() if line.startswith("|")]
+    return [r for r in rows if not set("".join(r)) <= set("-")]  # without the separator rows
+
+
+def test_sweep_tables_on_the_tiny_workload(P, capsys):
+    import paper_2604_12219_amd.sweeps as sweeps
+    sweeps.selection_histogram("tiny", 6, 1.0)  # a bias as large as the logit spread of this small workload
+    rows = _table_rows(capsys.readouterr().out)
+    assert [r[0] for r in rows[1:]] == ["deterministic", "stochastic, uniform bias", "stochastic, Gumbel bias"]
+    pct = lambda s: float(s.rstrip("%"))
+    for r in rows[1:]:
+        assert abs(pct(r[1]) + pct(r[2]) + pct(r[3]) + pct(r[4]) - 100.0) < 0.5   # the four classes partition the pairs
+        assert abs(pct(r[1]) + pct(r[5]) - 100.0) < 0.2                           # never + ever = all
+    det, sto = rows[1], rows[2]
+    assert pct(sto[5]) > pct(det[5])          # the seeded bias spreads the exact computation over more pairs ...
+    assert float(sto[6]) < float(det[6])      # ... each of which is selected in fewer steps
+    sweeps.sweep_noise("tiny")
+    rows = _table_rows(capsys.readouterr().out)
+    changed = [pct(r[1]) for r in rows[1:]]
+    assert changed[0] == 0.0 and all(a <= b + 1e-9 for a, b in zip(changed, changed[1:])) and changed[-1] > 5.0
+    sweeps.sweep_groups("tiny", 0.125, 1.0)
+    rows = _table_rows(capsys.readouterr().out)
+    assert [r[0] for r in rows[1:]] == ["0 (drop)", "1 (per block)", "16 (global)"] or rows[1][0] == "0 (drop)"
+    errs = {r[0]: float(r[5]) for r in rows[1:]}
+    assert errs["0 (drop)"] > errs["1 (per block)"]  # the approximation of the unselected blocks pays
