@@ -250,6 +250,9 @@ def main():
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-mfma-probe", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
+    ap.add_argument("--token-major", action="store_true",
+                    help="Q, K, V and O as [B,H,n,d] views of token-major storage [B,n,H,d] (what a transformer block hands over) "
+                         "instead of head-major storage (not the default path)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain device copy of Q (known size) so that hardware byte counters can be scaled")
     args = ap.parse_args()
@@ -271,6 +274,8 @@ def main():
     torch.cuda.set_device(dev)
     w = workloads.WORKLOADS[args.workload]
     q, k, v = workloads.make_workload_qkv(w, device=dev)
+    if args.token_major:  # the same values, rows of one head H*d elements apart
+        q, k, v = (t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for t in (q, k, v))
     shape = P.Shape.of(q, block=w.block, group=args.group, kv_slices=args.kv_slices)
     nb = P.num_blocks(shape)
     k_sel = P.topk_count(nb, w.keep_ratio)
@@ -354,7 +359,8 @@ def main():
                  for i, name in enumerate(("block_score", "route", "kv_stats"))} if not args.with_prior else None
     # bytes of K/V tiles the attention kernel asks for if no tile were reused between query blocks
     tile_bytes = bh * nb * k_sel * 2 * w.block * w.d * 2
-    traffic, traffic_source = measured_traffic(w.name, args.group) if args.kv_slices in (0, 1) and not args.with_prior else (None, "not the default path")
+    traffic, traffic_source = (measured_traffic(w.name, args.group) if args.kv_slices in (0, 1) and not args.with_prior and not args.token_major
+                               else (None, "not the default path"))
     # what a loop of nothing but MFMAs reaches on this device right now (the published peak assumes 2.4 GHz)
     mfma_loop = None if args.no_mfma_probe else P.mfma_probe()
     # ... and with N(0,1)-like operands in the registers: the matrix cores draw more power and the clock drops
@@ -374,7 +380,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "B": w.batch, "H": w.heads, "n": w.n, "d": w.d, "block": w.block,
                    "keep_ratio": w.keep_ratio, "k_sel": k_sel, "n_blocks": nb, "group": args.group,
-                   "noise_amp": args.noise_amp, "seed": w.seed, "kv_slices": args.kv_slices, "covariance_prior": args.with_prior},
+                   "noise_amp": args.noise_amp, "seed": w.seed, "kv_slices": args.kv_slices, "covariance_prior": args.with_prior,
+                   "layout": "token-major [B,n,H,d] storage" if args.token_major else "head-major [B,H,n,d] storage"},
         "ms_per_call_median": call_ms[len(call_ms) // 2], "ms_per_call_min": call_ms[0],
         "stage_ms": {"block_score": stage_ms[0], "route": stage_ms[1], "kv_stats": stage_ms[2], "sparse_attn": attn_ms},
         # the HBM-bound stages against the 8 TB/s peak: algorithmic bytes (inputs read once, outputs written once) / time
