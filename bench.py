@@ -2,9 +2,10 @@
 """Benchmark of the PASA sparse-attention forward on one MI355X.
 
 One "step" = one pass of the whole hot path over one synthetic batch already resident in HBM:
-  pasa_block_score -> pasa_route (fresh seed per step) -> pasa_kv_stats -> pasa_sparse_attn_fwd_prepared
-(the last two together are exactly what pasa_sparse_attn_fwd runs; they are issued separately only so
-that HIP events can bracket the attention kernel for the roofline figure).
+  pasa_kv_stats -> pasa_block_score_with_stats -> pasa_route (fresh seed per step) -> pasa_sparse_attn_fwd_prepared
+(the statistics do not depend on the queries, so they run first and scoring takes the block-mean keys from them instead of
+reading K again; statistics + prepared attention are exactly what pasa_sparse_attn_fwd runs, issued separately so that HIP
+events can bracket the attention kernel for the roofline figure).
 
 Prints ONE JSON line: dense-equivalent TFLOP/s (4*B*H*n^2*d / time) as `value`, ms per call, the roofline
 of the dominant kernel, and the CPU oracle timed on a bounded sample of the same workload.
@@ -169,11 +170,11 @@ def run_budget_schedule(args):
         q, k, v = inputs[s]
         idx = idx_buf[: bh * nb * ks[s]].view(bh, nb, ks[s])
         if events: events[0].record()
-        P.block_score(q, k, shape, scores=scores, ws=ws_score)
-        if events: events[1].record()
-        P.route(scores, ks[s], w.seed + s, args.noise_amp, idx=idx, mask=mask)
-        if events: events[2].record()
         P.kv_stats(k, v, shape, ws=ws_attn)
+        if events: events[1].record()
+        P.block_score(q, None, shape, scores=scores, ws=ws_score, stats_ws=ws_attn)
+        if events: events[2].record()
+        P.route(scores, ks[s], w.seed + s, args.noise_amp, idx=idx, mask=mask)
         if events: events[3].record()
         P.sparse_attn_fwd(q, k, v, shape, idx, mask, out=out, ws=ws_attn, prepared=True)
         if events: events[4].record()
@@ -218,7 +219,7 @@ def run_budget_schedule(args):
                    "k_sel_mean": sum(ks) / n_steps, "input_noise_amplitude": "1.0 -> 0.2, linear"},
         "total_ms": elapsed * 1e3,
         "per_step": {"k_sel": ks, "ms": [round(x, 4) for x in per_step_ms], "attn_ms": [round(x, 4) for x in attn_ms]},
-        "stage_ms_mean": {"block_score": stage_ms[0], "route": stage_ms[1], "kv_stats": stage_ms[2], "sparse_attn": stage_ms[3]},
+        "stage_ms_mean": {"kv_stats": stage_ms[0], "block_score": stage_ms[1], "route": stage_ms[2], "sparse_attn": stage_ms[3]},
         "buffers_allocated_once": True,
         "dense_ref_ms": dense_ms,
         "speedup_vs_dense_ref": (dense_ms * n_steps / (elapsed * 1e3)) if dense_ms else None,
@@ -302,13 +303,20 @@ def main():
             P.route(scores, k_sel, w.seed + i, args.noise_amp, idx=idx, mask=mask)
             if events: events[2].record()
             if events: events[3].record()
-        else:
+        elif args.group > 0:  # statistics first (they do not depend on the queries): scoring takes the block-mean keys from them
             if events: events[0].record()
-            P.block_score(q, k, shape, scores=scores, ws=ws_score)
-            if events: events[1].record()
-            P.route(scores, k_sel, w.seed + i, args.noise_amp, idx=idx, mask=mask)
-            if events: events[2].record()
             P.kv_stats(k, v, shape, ws=ws_attn)
+            if events: events[1].record()
+            P.block_score(q, None, shape, scores=scores, ws=ws_score, stats_ws=ws_attn)
+            if events: events[2].record()
+            P.route(scores, k_sel, w.seed + i, args.noise_amp, idx=idx, mask=mask)
+            if events: events[3].record()
+        else:  # approximation off: no statistics
+            if events: events[0].record()
+            if events: events[1].record()
+            P.block_score(q, k, shape, scores=scores, ws=ws_score)
+            if events: events[2].record()
+            P.route(scores, k_sel, w.seed + i, args.noise_amp, idx=idx, mask=mask)
             if events: events[3].record()
         P.sparse_attn_fwd(q, k, v, shape, idx, mask, out=out, ws=ws_attn, prepared=True)
         if events: events[4].record()
@@ -350,13 +358,19 @@ def main():
 
     qkv_bytes = w.batch * w.heads * w.n * w.d * 2
     score_bytes = bh * nb * nb * 4
-    stage_bytes = {"block_score": 2 * qkv_bytes + score_bytes + 2 * bh * nb * w.d * 4,
+    means_bytes = bh * nb * w.d * 4  # pooled means of one tensor (split bf16 pairs)
+    # which timed interval holds which stage (the covariance-prior path books the prior under block_score and runs the
+    # statistics before the first event)
+    slot = {"block_score": 0, "route": 1, "kv_stats": 2} if args.with_prior else {"kv_stats": 0, "block_score": 1, "route": 2}
+    stage = {name: stage_ms[i] for name, i in slot.items()}
+    reads_k = args.with_prior or args.group == 0  # otherwise scoring takes the block-mean keys from the statistics
+    stage_bytes = {"block_score": (2 if reads_k else 1) * qkv_bytes + score_bytes + 3 * means_bytes,
                    "route": score_bytes + bh * nb * (k_sel + P.mask_words(nb)) * 4,
-                   "kv_stats": 2 * qkv_bytes + (bh * (nb + 31) // 32 * 64 * w.d * 2 if args.group else 0)}
+                   "kv_stats": 2 * qkv_bytes + (bh * ((nb + 31) // 32) * 64 * w.d * 2 + means_bytes if args.group else 0)}
     stage_hbm = {name: {"algorithmic_GB": stage_bytes[name] / 1e9,
-                        "achieved_TBps": stage_bytes[name] / (stage_ms[i] * 1e-3) / 1e12,
-                        "frac_of_8TBps": stage_bytes[name] / (stage_ms[i] * 1e-3) / HBM_PEAK_BYTES_PER_S}
-                 for i, name in enumerate(("block_score", "route", "kv_stats"))} if not args.with_prior else None
+                        "achieved_TBps": stage_bytes[name] / (stage[name] * 1e-3) / 1e12,
+                        "frac_of_8TBps": stage_bytes[name] / (stage[name] * 1e-3) / HBM_PEAK_BYTES_PER_S}
+                 for name in ("block_score", "route", "kv_stats")} if not args.with_prior and args.group > 0 else None
     # bytes of K/V tiles the attention kernel asks for if no tile were reused between query blocks
     tile_bytes = bh * nb * k_sel * 2 * w.block * w.d * 2
     traffic, traffic_source = (measured_traffic(w.name, args.group) if args.kv_slices in (0, 1) and not args.with_prior and not args.token_major
@@ -383,7 +397,7 @@ def main():
                    "noise_amp": args.noise_amp, "seed": w.seed, "kv_slices": args.kv_slices, "covariance_prior": args.with_prior,
                    "layout": "token-major [B,n,H,d] storage" if args.token_major else "head-major [B,H,n,d] storage"},
         "ms_per_call_median": call_ms[len(call_ms) // 2], "ms_per_call_min": call_ms[0],
-        "stage_ms": {"block_score": stage_ms[0], "route": stage_ms[1], "kv_stats": stage_ms[2], "sparse_attn": attn_ms},
+        "stage_ms": {"kv_stats": stage["kv_stats"], "block_score": stage["block_score"], "route": stage["route"], "sparse_attn": attn_ms},
         # the HBM-bound stages against the 8 TB/s peak: algorithmic bytes (inputs read once, outputs written once) / time
         "stage_hbm": stage_hbm,
         "computed_tflops": computed_tflops,

@@ -6,6 +6,7 @@
  * every intermediate:
  *
  *   pasa_block_score      block-pooled Q/K routing logits             (Eq.8 without its row softmax)
+ *   pasa_block_score_with_stats  the same, with the block-mean keys taken from pasa_kv_stats' workspace
  *   pasa_key_prior        optional covariance prior of the routing logits (Eq.8, second term)
  *   pasa_route            seeded stochastic top-k block selection     (Eq.2 + Sec. "Stochastic Routing")
  *   pasa_route_gumbel     the same selection with a Gumbel-distributed bias (a variant)
@@ -115,6 +116,17 @@ PASA_API size_t pasa_attn_workspace_bytes(const pasa_shape_t* shape);
  */
 PASA_API int pasa_block_score(const void* q, const void* k, const pasa_shape_t* shape, const float* key_bias,
                      float* scores, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Stage 1 for callers that run pasa_kv_stats first (the statistics do not depend on the queries): the block-mean keys
+ * are taken from the statistics workspace instead of being pooled from K again, which saves one pass over K.
+ * Same scores as pasa_block_score up to the summation order of the key means (a few units in the last place).
+ *   stats_ws  the workspace pasa_kv_stats filled for the same k and shape (shape->group > 0: PASA_EUNSUPPORTED
+ *             otherwise), stats_ws_bytes its size; ws as for pasa_block_score (only the query half is used)
+ */
+PASA_API int pasa_block_score_with_stats(const void* q, const pasa_shape_t* shape, const float* key_bias, float* scores,
+                                         void* ws, size_t ws_bytes, const void* stats_ws, size_t stats_ws_bytes,
+                                         void* stream);
 
 /*
  * Stage 2 -- top-k routing with a seeded stochastic selection bias (Eq.2; Sec. "Stochastic Routing").

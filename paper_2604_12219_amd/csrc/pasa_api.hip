@@ -50,7 +50,7 @@ int check_group(int group, int nb) {
 float effective_scale(const pasa_shape_t* s) { return s->scale > 0.f ? s->scale : 1.0f / sqrtf((float)s->d); }
 
 struct AttnWorkspace {
-  size_t st, hg, partial, part_o, part_ml, queue, bitmap, total;
+  size_t st, hg, partial, kbar, part_o, part_ml, queue, bitmap, total;
   int n_groups, unit, n_units, n_chunks, n_slices;
 };
 
@@ -96,6 +96,7 @@ AttnWorkspace carve_attn(const pasa_shape_t* s) {
     w.st = off; off = align_up(off + bh * w.n_chunks * 64 * s->d * 2);
     w.hg = off; off = align_up(off + bh * w.n_groups * s->d * s->d * 2);
     w.partial = off; off = align_up(off + bh * w.n_units * s->d * s->d * 4);
+    w.kbar = off; off = align_up(off + bh * nb * s->d * 4);  // block-mean keys as split bf16 pairs, for pasa_block_score_with_stats
   }
   w.total = off;
   return w;
@@ -171,12 +172,12 @@ size_t pasa_attn_workspace_bytes(const pasa_shape_t* shape) {
   return t ? t : kAlign;  // never zero for a valid shape, so that 0 always means "bad shape"
 }
 
-int pasa_block_score(const void* q, const void* k, const pasa_shape_t* shape, const float* key_bias, float* scores,
-                     void* ws, size_t ws_bytes, void* stream) {
+static int block_score_impl(const void* q, const void* k, const pasa_shape_t* shape, const float* key_bias, float* scores,
+                            void* ws, size_t ws_bytes, const void* kbar_split, void* stream) {
   const int rc = check_shape(shape);
   if (rc != PASA_OK) return rc;
-  if (!q || !k || !scores || !ws) return PASA_EINVAL;
-  if (!aligned16(q) || !aligned16(k) || !aligned16(scores) || !aligned16(ws)) return PASA_EALIGN;
+  if (!q || (!k && !kbar_split) || !scores || !ws) return PASA_EINVAL;
+  if (!aligned16(q) || (k && !aligned16(k)) || !aligned16(scores) || !aligned16(ws)) return PASA_EALIGN;
   if (ws_bytes < pasa_score_workspace_bytes(shape)) return PASA_EWORKSPACE;
   ScoreParams p{};
   p.q = static_cast<const uint16_t*>(q);
@@ -187,9 +188,16 @@ int pasa_block_score(const void* q, const void* k, const pasa_shape_t* shape, co
   p.scale = effective_scale(shape);
   p.key_bias = key_bias;
   p.qbar = static_cast<float*>(ws);
-  p.kbar = reinterpret_cast<float*>(static_cast<char*>(ws) + pasa_score_workspace_bytes(shape) / 2);
+  p.pool_k = kbar_split ? 0 : 1;
+  p.kbar = kbar_split ? const_cast<float*>(static_cast<const float*>(kbar_split))
+                      : reinterpret_cast<float*>(static_cast<char*>(ws) + pasa_score_workspace_bytes(shape) / 2);
   p.scores = scores;
   return pasa_launch_block_score(p, static_cast<hipStream_t>(stream)) == hipSuccess ? PASA_OK : PASA_EHIP;
+}
+
+int pasa_block_score(const void* q, const void* k, const pasa_shape_t* shape, const float* key_bias, float* scores,
+                     void* ws, size_t ws_bytes, void* stream) {
+  return block_score_impl(q, k, shape, key_bias, scores, ws, ws_bytes, nullptr, stream);
 }
 
 static int route_impl(const float* scores, int32_t BH, int32_t n_blocks, int32_t k_sel, uint64_t seed, float noise_amp,
@@ -245,6 +253,16 @@ static int check_attn_args(const pasa_shape_t* shape, bool sparse, const void* w
   return PASA_OK;
 }
 
+int pasa_block_score_with_stats(const void* q, const pasa_shape_t* shape, const float* key_bias, float* scores, void* ws,
+                                size_t ws_bytes, const void* stats_ws, size_t stats_ws_bytes, void* stream) {
+  pasa_shape_t s;
+  const int rc = check_attn_args(shape, true, stats_ws, stats_ws_bytes, &s);
+  if (rc != PASA_OK) return rc;
+  if (s.group == 0) return PASA_EUNSUPPORTED;  // pasa_kv_stats leaves nothing when the approximation is off
+  const AttnWorkspace w = carve_attn(&s);
+  return block_score_impl(q, nullptr, shape, key_bias, scores, ws, ws_bytes, static_cast<const char*>(stats_ws) + w.kbar, stream);
+}
+
 int pasa_check_selection(const int32_t* idx, const uint32_t* mask, int32_t BH, int32_t n_blocks, int32_t k_sel, int32_t* n_bad,
                          void* stream) {
   if ((!idx && !mask) || !n_bad || BH < 1 || n_blocks < 1 || k_sel < 1 || k_sel > n_blocks) return PASA_EINVAL;
@@ -273,6 +291,7 @@ int pasa_kv_stats(const void* k, const void* v, const pasa_shape_t* shape, void*
   t.st = reinterpret_cast<uint16_t*>(base + w.st);
   t.hg = reinterpret_cast<uint16_t*>(base + w.hg);
   t.partial = reinterpret_cast<float*>(base + w.partial);
+  t.kbar_split = reinterpret_cast<uint16_t*>(base + w.kbar);
   return pasa_launch_kv_stats(t, static_cast<hipStream_t>(stream)) == hipSuccess ? PASA_OK : PASA_EHIP;
 }
 

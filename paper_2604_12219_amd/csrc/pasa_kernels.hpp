@@ -48,6 +48,8 @@ struct StatsParams {
   uint16_t* st;      // out bf16 [BH][n_chunks][64][d] (see AttnParams::st)
   float* partial;    // scratch fp32 [BH][n_units][d][d]: sum over the unit's blocks of H_j
   uint16_t* hg;      // out bf16 [BH][n_groups][d][d] (see AttnParams::hg)
+  uint16_t* kbar_split;  // out [BH][nb][d] x 4 bytes: block-mean keys as split bf16 pairs in the score kernel's layout
+                         // (per 32 elements 32 x hi then 32 x lo), so that scoring need not read K again
 };
 hipError_t pasa_launch_kv_stats(const StatsParams& p, hipStream_t stream);
 // beta [BH][nb] fp32 = log(||H_j - Hg_{g(j)}||_F + eps); needs p.partial as pasa_launch_kv_stats left it
@@ -63,6 +65,7 @@ struct ScoreParams {
   float* qbar;            // scratch [BH][nb][d] x 4 bytes: block means as split bf16 pairs, per 32 elements 32 x hi then 32 x lo
   float* kbar;            // the same for the keys
   float* scores;          // out fp32 [BH][nb][nb]
+  int32_t pool_k;         // 1: pool the keys here; 0: kbar already holds the split block-mean keys (left by the statistics kernel)
 };
 hipError_t pasa_launch_block_score(const ScoreParams& p, hipStream_t stream);
 

@@ -159,7 +159,7 @@ __global__ void __launch_bounds__(256) score_gemm_kernel(ScoreParams p, int runs
 }  // namespace
 
 hipError_t pasa_launch_block_score(const ScoreParams& p, hipStream_t stream) {
-  const dim3 gp(p.nb, p.bh, 2);
+  const dim3 gp(p.nb, p.bh, p.pool_k ? 2 : 1);  // z = 0 pools the queries, z = 1 the keys
   const int tiles = (p.nb + 63) / 64;
   // strips of 64 rows; a strip is cut into runs of column tiles only as far as it takes to fill the device
   const int64_t strips = (int64_t)tiles * p.bh;

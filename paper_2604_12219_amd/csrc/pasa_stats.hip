@@ -123,6 +123,13 @@ __global__ void __launch_bounds__(256, 2) kv_stats_kernel(StatsParams p) {
 #pragma unroll
           for (int r = 0; r < 4; ++r) m4[r] = (__bf16)(ksum[a][4 * g + r] * inv_len);
           *reinterpret_cast<bf16x4*>(strow + 32 * (tin0 + a) + 8 * g + 4 * h) = m4;
+          // the same means as split bf16 pairs (hi + lo, 16 significant bits) for the score kernel
+          bf16x4 lo4;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) lo4[r] = (__bf16)(ksum[a][4 * g + r] * inv_len - (float)m4[r]);
+          uint16_t* const krow = p.kbar_split + ((int64_t)bh * p.nb + j) * (2 * D) + 64 * (tin0 + a) + 8 * g + 4 * h;
+          *reinterpret_cast<bf16x4*>(krow) = m4;
+          *reinterpret_cast<bf16x4*>(krow + 32) = lo4;
         }
       }
     }

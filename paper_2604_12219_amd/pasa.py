@@ -16,7 +16,7 @@ _LIB_PATH = os.path.join(_HERE, "libpasa_hip.so")
 _lib = None
 
 EXPORTS = ("pasa_strerror", "pasa_topk_count", "pasa_num_blocks", "pasa_mask_words", "pasa_score_workspace_bytes",
-           "pasa_attn_workspace_bytes", "pasa_block_score", "pasa_route", "pasa_route_gumbel", "pasa_kv_stats", "pasa_key_prior", "pasa_sparse_attn_fwd",
+           "pasa_attn_workspace_bytes", "pasa_block_score", "pasa_block_score_with_stats", "pasa_route", "pasa_route_gumbel", "pasa_kv_stats", "pasa_key_prior", "pasa_sparse_attn_fwd",
            "pasa_sparse_attn_fwd_prepared", "pasa_sparse_attn_fwd_static", "pasa_check_selection", "pasa_attn_dense_ref", "pasa_l1_workspace_bytes", "pasa_l1_distance",
            "pasa_budget_schedule", "pasa_mfma_probe")
 
@@ -88,6 +88,8 @@ def load_library() -> ctypes.CDLL:
         L.pasa_attn_workspace_bytes.argtypes = [sp]
         L.pasa_block_score.restype = ctypes.c_int
         L.pasa_block_score.argtypes = [vp, vp, sp, vp, vp, vp, ctypes.c_size_t, vp]
+        L.pasa_block_score_with_stats.restype = ctypes.c_int
+        L.pasa_block_score_with_stats.argtypes = [vp, sp, vp, vp, vp, ctypes.c_size_t, vp, ctypes.c_size_t, vp]
         L.pasa_route.restype = ctypes.c_int
         L.pasa_route.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_uint64, ctypes.c_float,
                                  vp, vp, vp]
@@ -166,13 +168,18 @@ def _workspace(nbytes: int, device, ws):
     return ws
 
 
-def block_score(q, k, shape: Shape, key_bias=None, scores=None, ws=None):
-    """-> scores fp32 [B*H, N_B, N_B]"""
+def block_score(q, k, shape: Shape, key_bias=None, scores=None, ws=None, stats_ws=None):
+    """-> scores fp32 [B*H, N_B, N_B].  With stats_ws (the workspace kv_stats() filled for the same k and shape) the
+    block-mean keys are taken from there and K is not read (k may be None)."""
     L = load_library()
     nb = num_blocks(shape)
     if scores is None:
         scores = torch.empty((shape.B * shape.H, nb, nb), dtype=torch.float32, device=q.device)
     ws = _workspace(score_workspace_bytes(shape), q.device, ws)
+    if stats_ws is not None:
+        _check(L.pasa_block_score_with_stats(_ptr(q), ctypes.byref(shape.c()), _ptr(key_bias), _ptr(scores), _ptr(ws), ws.numel(),
+                                             _ptr(stats_ws), stats_ws.numel(), _stream()), "pasa_block_score_with_stats")
+        return scores
     _check(L.pasa_block_score(_ptr(q), _ptr(k), ctypes.byref(shape.c()), _ptr(key_bias), _ptr(scores), _ptr(ws),
                               ws.numel(), _stream()), "pasa_block_score")
     return scores

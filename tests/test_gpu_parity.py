@@ -71,6 +71,36 @@ def test_block_scores_match_oracle(P, grid, d, block):
     np.testing.assert_allclose(s1.cpu().numpy(), ref + bias.cpu().numpy()[:, None, :], atol=tol, rtol=0)
 
 
+@pytest.mark.parametrize("grid,d,block,group", [((4, 16, 16), 64, 64, 32), ((3, 21, 13), 128, 64, 32), ((3, 21, 13), 128, 128, 8),
+                                                ((9, 20, 23), 128, 64, 64), ((9, 20, 23), 64, 64, 1000), ((1, 5, 7), 128, 64, 32)])
+def test_block_scores_from_the_statistics_workspace(P, grid, d, block, group):
+    """pasa_block_score_with_stats: the block-mean keys come from pasa_kv_stats' workspace, K is not read again"""
+    q, k, v = _inputs(grid, 2, d, seed=3)
+    shape = P.Shape.of(q, block=block, group=group)
+    nb = P.num_blocks(shape)
+    bias = torch.randn((2, nb), device="cuda", generator=torch.Generator("cuda").manual_seed(2))
+    ws = P.kv_stats(k, v, shape)
+    s0 = P.block_score(q, None, shape, stats_ws=ws)
+    s1 = P.block_score(q, None, shape, key_bias=bias, stats_ws=ws)
+    plain = P.block_score(q, k, shape)
+    torch.cuda.synchronize()
+    ref = oracle.block_scores(to_f64(q), to_f64(k), block)
+    tol = 1e-3 * np.abs(ref).max()
+    np.testing.assert_allclose(s0.cpu().numpy(), ref, atol=tol, rtol=0)
+    np.testing.assert_allclose(s1.cpu().numpy(), ref + bias.cpu().numpy()[:, None, :], atol=tol, rtol=0)
+    # the two routes to the scores differ only by the summation order of the key means
+    np.testing.assert_allclose(s0.cpu().numpy(), plain.cpu().numpy(), atol=2e-5 * np.abs(ref).max(), rtol=0)
+    # the statistics workspace still serves the attention kernel afterwards
+    k_sel = P.topk_count(nb, 0.3)
+    idx, mask = P.route(s0, k_sel, 5, 0.1)
+    out = P.sparse_attn_fwd(q, k, v, shape, idx, mask, ws=ws, prepared=True)
+    torch.cuda.synchronize()
+    res = oracle.pasa_attention(to_f64(q), to_f64(k), to_f64(v), idx.cpu().numpy(), block, group=group)
+    assert_close(to_f64(out), res, what="attention after scoring from the statistics")
+    with pytest.raises(P.PasaError):  # approximation off: the statistics call leaves no key means
+        P.block_score(q, None, P.Shape.of(q, block=block, group=0), stats_ws=ws)
+
+
 @pytest.mark.parametrize("grid,d,block,group", [((4, 16, 16), 64, 64, 32), ((5, 21, 13), 128, 64, 8),
                                                 ((9, 20, 23), 128, 64, 32), ((9, 20, 23), 128, 64, 64),
                                                 ((9, 20, 23), 128, 64, 1000), ((9, 20, 23), 128, 128, 32),
