@@ -127,6 +127,21 @@ def _ptr(t):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
 
 
+def _check_extent(shape: "Shape", **tensors):
+    """host-side bounds check of the marshalled arguments: the last element the kernels may touch through the strides
+    of `shape` (batch B-1, head H-1, token n-1, column d-1; no token >= n is ever read or written) must lie inside
+    the tensor's storage"""
+    last = (shape.B - 1) * shape.stride_b + (shape.H - 1) * shape.stride_h + (shape.n - 1) * shape.stride_n + shape.d - 1
+    for name, t in tensors.items():
+        if t is None:
+            continue
+        if t.dtype != torch.bfloat16:
+            raise ValueError(f"{name}: expected bf16, got {t.dtype}")
+        room = t.untyped_storage().nbytes() // t.element_size() - t.storage_offset()
+        if last >= room:
+            raise ValueError(f"{name}: the shape's strides reach element {last} of a storage that holds {room} from the tensor's start")
+
+
 def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
@@ -176,6 +191,7 @@ def block_score(q, k, shape: Shape, key_bias=None, scores=None, ws=None, stats_w
     if scores is None:
         scores = torch.empty((shape.B * shape.H, nb, nb), dtype=torch.float32, device=q.device)
     ws = _workspace(score_workspace_bytes(shape), q.device, ws)
+    _check_extent(shape, q=q, k=k)
     if stats_ws is not None:
         _check(L.pasa_block_score_with_stats(_ptr(q), ctypes.byref(shape.c()), _ptr(key_bias), _ptr(scores), _ptr(ws), ws.numel(),
                                              _ptr(stats_ws), stats_ws.numel(), _stream()), "pasa_block_score_with_stats")
@@ -216,6 +232,7 @@ def kv_stats(k, v, shape: Shape, ws=None):
     """fills (and returns) the attention workspace with the key/value block statistics"""
     L = load_library()
     ws = _workspace(attn_workspace_bytes(shape), k.device, ws)
+    _check_extent(shape, k=k, v=v)
     _check(L.pasa_kv_stats(_ptr(k), _ptr(v), ctypes.byref(shape.c()), _ptr(ws), ws.numel(), _stream()), "pasa_kv_stats")
     return ws
 
@@ -271,6 +288,7 @@ def sparse_attn_fwd(q, k, v, shape: Shape, idx, mask, out=None, lse=None, ws=Non
     if lse is None and want_lse:
         lse = torch.empty((shape.B * shape.H, shape.n), dtype=torch.float32, device=q.device)
     ws = _workspace(attn_workspace_bytes(shape), q.device, ws)
+    _check_extent(shape, q=q, k=k, v=v, out=out)
     fn = L.pasa_sparse_attn_fwd_prepared if prepared else L.pasa_sparse_attn_fwd
     k_sel = idx.shape[-1] if idx is not None else int(k_sel)
     _check(fn(_ptr(q), _ptr(k), _ptr(v), ctypes.byref(shape.c()), _ptr(idx), _ptr(mask), k_sel, _ptr(out),
@@ -283,6 +301,7 @@ STATIC_SCRATCH_BYTES = 64 << 20  # PASA_STATIC_SCRATCH_BYTES of pasa.h
 
 def sparse_attn_fwd_static(q, k, v, shape: Shape, idx, mask, out, lse=None):
     """pasa_sparse_attn_fwd_static: the caller passes inputs and outputs only; nothing is allocated, here or in the library"""
+    _check_extent(shape, q=q, k=k, v=v, out=out)
     _check(load_library().pasa_sparse_attn_fwd_static(_ptr(q), _ptr(k), _ptr(v), ctypes.byref(shape.c()), _ptr(idx), _ptr(mask),
                                                       idx.shape[-1], _ptr(out), _ptr(lse), _stream()),
            "pasa_sparse_attn_fwd_static")
@@ -296,6 +315,7 @@ def attn_dense_ref(q, k, v, shape: Shape, out=None, lse=None, ws=None, want_lse:
     if lse is None and want_lse:
         lse = torch.empty((shape.B * shape.H, shape.n), dtype=torch.float32, device=q.device)
     ws = _workspace(attn_workspace_bytes(shape), q.device, ws)
+    _check_extent(shape, q=q, k=k, v=v, out=out)
     _check(L.pasa_attn_dense_ref(_ptr(q), _ptr(k), _ptr(v), ctypes.byref(shape.c()), _ptr(out), _ptr(lse), _ptr(ws),
                                  ws.numel(), _stream()), "pasa_attn_dense_ref")
     return (out, lse) if want_lse else out

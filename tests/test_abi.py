@@ -203,3 +203,22 @@ def test_budget_schedule_host_function_matches_oracle_and_rejects_bad_input():
     r = P.budget_schedule(g.uniform(0.5, 1.5, size=(10, 50)), 0.15)
     ks = [P.topk_count(1182, x) for x in r]
     assert ks[:10] == [1182] * 10 and all(1 <= k <= 1182 for k in ks) and abs(sum(ks[10:]) - 0.15 * 1182 * 40) < 40
+
+
+def test_binding_checks_that_the_strides_stay_inside_the_tensors():
+    """host-side bounds check of the binding: a shape whose strides reach beyond a tensor's storage is refused before
+    any library call (CPU tensors will do: the check never touches the data)"""
+    import torch
+    import paper_2604_12219_amd.pasa as mod
+    q = torch.zeros((1, 2, 100, 64), dtype=torch.bfloat16)
+    shape = mod.Shape.of(q)
+    mod._check_extent(shape, q=q, k=q, v=None)  # fits exactly
+    longer = mod.Shape(1, 2, 101, 64, 64, 32, shape.stride_b, shape.stride_h, shape.stride_n)
+    with pytest.raises(ValueError, match="reach element"):
+        mod._check_extent(longer, q=q)
+    view = q[:, :, 10:]  # a view that starts later in the same storage has less room
+    with pytest.raises(ValueError, match="reach element"):
+        mod._check_extent(shape, q=view)
+    mod._check_extent(mod.Shape.of(view), q=view)
+    with pytest.raises(ValueError, match="bf16"):
+        mod._check_extent(shape, q=q.float())
