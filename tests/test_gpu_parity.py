@@ -435,3 +435,47 @@ def test_sweep_tables_on_the_tiny_workload(P, capsys):
     assert [r[0] for r in rows[1:]] == ["0 (drop)", "1 (per block)", "16 (global)"] or rows[1][0] == "0 (drop)"
     errs = {r[0]: float(r[5]) for r in rows[1:]}
     assert errs["0 (drop)"] > errs["1 (per block)"]  # the approximation of the unselected blocks pays
+
+
+# ------------------------------------------------------------------------------------------------
+# seeded random configurations: shapes, strides, block and group sizes, keep ratios drawn at random
+# ------------------------------------------------------------------------------------------------
+def _random_config(rng):
+    d = int(rng.choice([64, 128]))
+    block = int(rng.choice([64, 128]))
+    n = int(rng.integers(1, 2600))
+    nb = (n + block - 1) // block
+    group = int(rng.choice([0, 1, 2, 4, 8, 16, 32, 64, 10_000]))
+    keep = float(rng.choice([0.02, 0.1, 0.25, 0.5, 0.9, 1.0]))
+    heads, batch = int(rng.integers(1, 4)), int(rng.integers(1, 3))
+    token_major = bool(rng.integers(0, 2))
+    scale = float(rng.choice([0.0, 0.05, 0.2]))
+    return dict(d=d, block=block, n=n, nb=nb, group=group, keep=keep, heads=heads, batch=batch, token_major=token_major, scale=scale)
+
+
+@pytest.mark.parametrize("case", range(24))
+def test_random_configurations_against_oracle(P, case):
+    rng = np.random.default_rng(1000 + case)
+    c = _random_config(rng)
+    q, k, v = workloads.make_qkv((1, 1, c["n"]), c["heads"], c["d"], seed=case, device="cuda", batch=c["batch"])
+    if c["token_major"]:
+        q, k, v = (t.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3) for t in (q, k, v))
+    shape = P.Shape.of(q, block=c["block"], group=c["group"], scale=c["scale"])
+    k_sel = P.topk_count(c["nb"], c["keep"])
+    scale = c["scale"] if c["scale"] > 0 else None
+    ws = P.kv_stats(k, v, shape)
+    scores = P.block_score(q, None, shape, stats_ws=ws) if c["group"] > 0 else P.block_score(q, k, shape)
+    idx, mask = P.route(scores, k_sel, 7 * case + 1, 0.3)
+    out, lse = P.sparse_attn_fwd(q, k, v, shape, idx, mask, want_lse=True)
+    dense = P.attn_dense_ref(q, k, v, shape)
+    torch.cuda.synchronize()
+    what = f"case {case}: {c}"
+    assert P.check_selection(idx, mask, c["nb"], k_sel).item() == 0, what
+    ref_scores = oracle.block_scores(to_f64(q), to_f64(k), c["block"], scale=scale)
+    np.testing.assert_allclose(scores.cpu().numpy(), ref_scores, atol=1e-3 * max(np.abs(ref_scores).max(), 1e-3), rtol=0, err_msg=what)
+    np.testing.assert_array_equal(idx.cpu().numpy(), oracle.route(scores.cpu().numpy(), k_sel, 7 * case + 1, 0.3), err_msg=what)
+    res = oracle.pasa_attention(to_f64(q), to_f64(k), to_f64(v), idx.cpu().numpy(), c["block"], group=c["group"], scale=scale,
+                                return_all=True)
+    assert_close(to_f64(out), res["o"], what=what)
+    np.testing.assert_allclose(lse.cpu().numpy(), res["lse"], atol=2e-2, err_msg=what)
+    assert_close(to_f64(dense), oracle.dense_attention(to_f64(q), to_f64(k), to_f64(v), scale=scale), what="dense, " + what)
