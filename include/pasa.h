@@ -231,7 +231,7 @@ PASA_API int pasa_check_selection(const int32_t* idx, const uint32_t* mask, int3
  * nothing and calls no allocating routine; its first call on a device looks the buffer's address up once (make
  * that call outside a graph capture).  shape->kv_slices is ignored (no slicing).
  *   PASA_ESCRATCH if pasa_attn_workspace_bytes(shape with kv_slices = 1) > PASA_STATIC_SCRATCH_BYTES
- *   (e.g. the Wan-1.3B 480p shape, 12 heads of 32,760 tokens, needs 58 MiB; 40 heads of 75,600 tokens do not fit).
+ *   (e.g. the Wan-1.3B 480p shape, 12 heads of 32,760 tokens, needs 61 MiB; 40 heads of 75,600 tokens do not fit).
  * All calls on one GPU share the buffer: two calls that overlap in time on one GPU (different streams, or
  * different host threads) race and give wrong results.  Nothing in it has to be cleared between calls (every
  * part is rewritten before it is read).
