@@ -14,6 +14,7 @@
  *   pasa_sparse_attn_fwd  exact attention over the selected blocks + grouped Taylor approximation
  *                         of the unselected ones under one normaliser (Eq.7, Eq.4, Eq.5, Eq.12, Eq.14)
  *   pasa_attn_dense_ref   dense attention with the same tile machinery (Eq.1)
+ *   pasa_forward          statistics, scores, routing and piecewise attention in one call
  *
  * Conventions
  *   - Every pointer is a DEVICE pointer unless marked "host".  The caller owns every buffer; the
@@ -210,6 +211,20 @@ PASA_API int pasa_sparse_attn_fwd(const void* q, const void* k, const void* v, c
 PASA_API int pasa_sparse_attn_fwd_prepared(const void* q, const void* k, const void* v, const pasa_shape_t* shape,
                                            const int32_t* idx, const uint32_t* mask, int32_t k_sel, void* out,
                                            float* lse, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * The whole forward in one call: statistics, scores (routing logit without the covariance prior), routing with the
+ * uniform selection bias, piecewise attention -- exactly the sequence pasa_kv_stats, pasa_block_score_with_stats,
+ * pasa_route(k_sel = pasa_topk_count(N_B, keep_ratio)), pasa_sparse_attn_fwd_prepared, with every intermediate
+ * (scores, index lists, bitmap, both scratch areas) carved out of one workspace.  Callers that want the
+ * intermediates, the prior, the Gumbel bias or their own selection use the stage entry points instead.
+ *   keep_ratio in (0, 1]; seed, noise_amp as in pasa_route; out, lse as in pasa_sparse_attn_fwd
+ *   ws  pasa_forward_workspace_bytes(shape, keep_ratio) bytes (host-only helper; 0 on invalid arguments), 256-byte aligned
+ * N_B <= 4096 (the limit of pasa_route).
+ */
+PASA_API size_t pasa_forward_workspace_bytes(const pasa_shape_t* shape, double keep_ratio);
+PASA_API int pasa_forward(const void* q, const void* k, const void* v, const pasa_shape_t* shape, double keep_ratio,
+                          uint64_t seed, float noise_amp, void* out, float* lse, void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Validation of a selection before it is handed to pasa_sparse_attn_fwd (debugging aid for callers that build

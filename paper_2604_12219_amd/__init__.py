@@ -14,6 +14,7 @@ from .pasa import (  # noqa: F401
     check_selection,
     budget_schedule,
     forward,
+    forward_single_call,
     key_prior,
     kv_stats,
     l1_distance,

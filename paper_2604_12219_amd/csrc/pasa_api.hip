@@ -394,6 +394,72 @@ int pasa_sparse_attn_fwd_static(const void* q, const void* k, const void* v, con
   return attn_common(q, k, v, &s, idx, mask, k_sel, out, lse, ws, (size_t)PASA_STATIC_SCRATCH_BYTES, stream, true, true);
 }
 
+// ---- the whole forward in one call ---------------------------------------------------------------
+namespace {
+struct ForwardWorkspace {
+  size_t scores, idx, mask, score_ws, attn_ws, total;
+  int nb, k_sel;
+};
+
+// 0 in `total` on invalid arguments
+ForwardWorkspace carve_forward(const pasa_shape_t* s, double keep_ratio) {
+  ForwardWorkspace f{};
+  if (check_shape(s) != PASA_OK) return f;
+  f.nb = num_blocks(s);
+  const int32_t k = pasa_topk_count(f.nb, keep_ratio);
+  if (k < 1) return f;
+  f.k_sel = k;
+  pasa_shape_t a = *s;
+  const size_t attn = pasa_attn_workspace_bytes(&a), score = pasa_score_workspace_bytes(&a);
+  if (attn == 0 || score == 0) return f;
+  const size_t bh = (size_t)s->B * s->H;
+  size_t off = 0;
+  f.scores = off; off = align_up(off + bh * f.nb * f.nb * 4);
+  f.idx = off; off = align_up(off + bh * f.nb * (size_t)k * 4);
+  f.mask = off; off = align_up(off + bh * f.nb * (size_t)((f.nb + 31) / 32) * 4);
+  f.score_ws = off; off = align_up(off + score);
+  f.attn_ws = off; off = align_up(off + attn);
+  f.total = off;
+  return f;
+}
+}  // namespace
+
+size_t pasa_forward_workspace_bytes(const pasa_shape_t* shape, double keep_ratio) { return carve_forward(shape, keep_ratio).total; }
+
+int pasa_forward(const void* q, const void* k, const void* v, const pasa_shape_t* shape, double keep_ratio, uint64_t seed,
+                 float noise_amp, void* out, float* lse, void* ws, size_t ws_bytes, void* stream) {
+  const int rc = check_shape(shape);
+  if (rc != PASA_OK) return rc;
+  if (!(keep_ratio > 0.0) || keep_ratio > 1.0) return PASA_EINVAL;
+  const int rg = check_group(shape->group, num_blocks(shape));
+  if (rg != PASA_OK) return rg;
+  const int rs = check_slices(shape);
+  if (rs != PASA_OK) return rs;
+  const ForwardWorkspace f = carve_forward(shape, keep_ratio);
+  if (f.total == 0) return PASA_EUNSUPPORTED;
+  if (!q || !k || !v || !out || !ws) return PASA_EINVAL;
+  if (!aligned16(ws)) return PASA_EALIGN;
+  if (ws_bytes < f.total) return PASA_EWORKSPACE;
+  if (f.nb > kRouteMaxBlocks) return PASA_EUNSUPPORTED;
+  char* base = static_cast<char*>(ws);
+  float* scores = reinterpret_cast<float*>(base + f.scores);
+  int32_t* idx = reinterpret_cast<int32_t*>(base + f.idx);
+  uint32_t* mask = reinterpret_cast<uint32_t*>(base + f.mask);
+  const size_t attn_bytes = pasa_attn_workspace_bytes(shape), score_bytes = pasa_score_workspace_bytes(shape);
+  int r;
+  if (shape->group > 0) {  // the statistics first: scoring takes the block-mean keys from them
+    r = pasa_kv_stats(k, v, shape, base + f.attn_ws, attn_bytes, stream);
+    if (r != PASA_OK) return r;
+    r = pasa_block_score_with_stats(q, shape, nullptr, scores, base + f.score_ws, score_bytes, base + f.attn_ws, attn_bytes, stream);
+  } else {
+    r = pasa_block_score(q, k, shape, nullptr, scores, base + f.score_ws, score_bytes, stream);
+  }
+  if (r != PASA_OK) return r;
+  r = pasa_route(scores, shape->B * shape->H, f.nb, f.k_sel, seed, noise_amp, idx, mask, stream);
+  if (r != PASA_OK) return r;
+  return pasa_sparse_attn_fwd_prepared(q, k, v, shape, idx, mask, f.k_sel, out, lse, base + f.attn_ws, attn_bytes, stream);
+}
+
 int pasa_attn_dense_ref(const void* q, const void* k, const void* v, const pasa_shape_t* shape, void* out, float* lse,
                         void* ws, size_t ws_bytes, void* stream) {
   return attn_common(q, k, v, shape, nullptr, nullptr, 0, out, lse, ws, ws_bytes, stream, false, false);

@@ -17,7 +17,7 @@ _lib = None
 
 EXPORTS = ("pasa_strerror", "pasa_topk_count", "pasa_num_blocks", "pasa_mask_words", "pasa_score_workspace_bytes",
            "pasa_attn_workspace_bytes", "pasa_block_score", "pasa_block_score_with_stats", "pasa_route", "pasa_route_gumbel", "pasa_kv_stats", "pasa_key_prior", "pasa_sparse_attn_fwd",
-           "pasa_sparse_attn_fwd_prepared", "pasa_sparse_attn_fwd_static", "pasa_check_selection", "pasa_attn_dense_ref", "pasa_l1_workspace_bytes", "pasa_l1_distance",
+           "pasa_sparse_attn_fwd_prepared", "pasa_sparse_attn_fwd_static", "pasa_forward", "pasa_forward_workspace_bytes", "pasa_check_selection", "pasa_attn_dense_ref", "pasa_l1_workspace_bytes", "pasa_l1_distance",
            "pasa_budget_schedule", "pasa_mfma_probe")
 
 
@@ -104,6 +104,10 @@ def load_library() -> ctypes.CDLL:
         L.pasa_sparse_attn_fwd_prepared.argtypes = L.pasa_sparse_attn_fwd.argtypes
         L.pasa_sparse_attn_fwd_static.restype = ctypes.c_int
         L.pasa_sparse_attn_fwd_static.argtypes = [vp, vp, vp, sp, vp, vp, ctypes.c_int32, vp, vp, vp]
+        L.pasa_forward_workspace_bytes.restype = ctypes.c_size_t
+        L.pasa_forward_workspace_bytes.argtypes = [sp, ctypes.c_double]
+        L.pasa_forward.restype = ctypes.c_int
+        L.pasa_forward.argtypes = [vp, vp, vp, sp, ctypes.c_double, ctypes.c_uint64, ctypes.c_float, vp, vp, vp, ctypes.c_size_t, vp]
         L.pasa_check_selection.restype = ctypes.c_int
         L.pasa_check_selection.argtypes = [vp, vp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, vp, vp]
         L.pasa_kv_stats.restype = ctypes.c_int
@@ -345,6 +349,24 @@ def forward(q, k, v, keep_ratio: float, seed: int, noise_amp: float, block: int 
     route(b["scores"], k_sel, seed, noise_amp, idx=b["idx"], mask=b["mask"])
     sparse_attn_fwd(q, k, v, shape, b["idx"], b["mask"], out=b["out"], ws=b["ws_attn"])
     return b["out"], b["idx"]
+
+
+def forward_single_call(q, k, v, shape: Shape, keep_ratio: float, seed: int, noise_amp: float, out=None, lse=None, ws=None,
+                        want_lse: bool = False):
+    """pasa_forward: the whole path in one library call, every intermediate inside one workspace"""
+    L = load_library()
+    nbytes = int(L.pasa_forward_workspace_bytes(ctypes.byref(shape.c()), float(keep_ratio)))
+    if nbytes == 0:
+        raise PasaError(-1, "pasa_forward_workspace_bytes")
+    ws = _workspace(nbytes, q.device, ws)
+    if out is None:
+        out = torch.empty_like(q)
+    if lse is None and want_lse:
+        lse = torch.empty((shape.B * shape.H, shape.n), dtype=torch.float32, device=q.device)
+    _check_extent(shape, q=q, k=k, v=v, out=out)
+    _check(L.pasa_forward(_ptr(q), _ptr(k), _ptr(v), ctypes.byref(shape.c()), float(keep_ratio), seed & (2**64 - 1), noise_amp,
+                          _ptr(out), _ptr(lse), _ptr(ws), ws.numel(), _stream()), "pasa_forward")
+    return (out, lse) if want_lse else out
 
 
 def mfma_probe(workgroups: int = 4096, iterations: int = 4096, reps: int = 3, random_operands: bool = False) -> float:

@@ -159,6 +159,20 @@ def test_argument_validation_returns_before_any_launch(P):
     assert static(good, q=None) == EINVAL and static(good, k=0) == EINVAL and static(good, k=129) == EINVAL
     assert static(_shape(P, group=48).c()) == EUNSUPPORTED and static(_shape(P, d=96).c()) == EUNSUPPORTED
     assert b"static" in L.pasa_strerror(ESCRATCH)
+    # the whole forward in one call
+    fwd_bytes = L.pasa_forward_workspace_bytes
+    assert fwd_bytes(ctypes.byref(good), 0.15) > P.attn_workspace_bytes(_shape(P)) + P.score_workspace_bytes(_shape(P))
+    assert fwd_bytes(ctypes.byref(good), 0.0) == 0 and fwd_bytes(ctypes.byref(good), 1.5) == 0
+    assert fwd_bytes(ctypes.byref(_shape(P, d=96).c()), 0.15) == 0
+
+    def forward(shape, keep=0.15, q=fake, out=ctypes.c_void_p(0x2000), ws=fake, nbytes=big):
+        return L.pasa_forward(q, fake, fake, ctypes.byref(shape), ctypes.c_double(keep), 7, ctypes.c_float(0.1), out, None, ws, nbytes, None)
+
+    assert forward(good, keep=0.0) == EINVAL and forward(good, keep=float("nan")) == EINVAL
+    assert forward(good, q=None) == EINVAL and forward(good, ws=None) == EINVAL
+    assert forward(good, nbytes=ctypes.c_size_t(1024)) == EWORKSPACE
+    assert forward(_shape(P, group=48).c()) == EUNSUPPORTED
+    assert forward(_shape(P, n=5000 * 64).c()) == EUNSUPPORTED  # more key blocks than the routing kernel takes
     for code in (0, -1, -2, -3, -4, -5, -6, -99):
         assert isinstance(L.pasa_strerror(code), bytes) and len(L.pasa_strerror(code)) > 0
 

@@ -338,6 +338,25 @@ def test_batch_and_heads_are_independent_and_results_are_deterministic(P):
     assert_close(to_f64(out), ref, what="batch=2")
 
 
+@pytest.mark.parametrize("grid,d,block,group,keep", [((4, 16, 16), 64, 64, 32, 0.25), ((9, 20, 23), 128, 64, 32, 0.15),
+                                                     ((9, 20, 23), 128, 128, 8, 0.3), ((5, 21, 13), 128, 64, 0, 0.2)])
+def test_single_call_forward_equals_the_stage_calls(P, grid, d, block, group, keep):
+    """pasa_forward against the four stage entry points (bit for bit: the same kernels in the same order) and the oracle"""
+    q, k, v = _inputs(grid, 2, d, seed=31)
+    shape = P.Shape.of(q, block=block, group=group)
+    nb = P.num_blocks(shape)
+    k_sel = P.topk_count(nb, keep)
+    out, lse = P.forward_single_call(q, k, v, shape, keep, 123, 0.2, want_lse=True)
+    ws = P.kv_stats(k, v, shape)
+    scores = P.block_score(q, None, shape, stats_ws=ws) if group > 0 else P.block_score(q, k, shape)
+    idx, mask = P.route(scores, k_sel, 123, 0.2)
+    want, want_lse = P.sparse_attn_fwd(q, k, v, shape, idx, mask, ws=ws, prepared=True, want_lse=True)
+    torch.cuda.synchronize()
+    assert torch.equal(out, want) and torch.equal(lse, want_lse)
+    ref = oracle.pasa_attention(to_f64(q), to_f64(k), to_f64(v), idx.cpu().numpy(), block, group=group)
+    assert_close(to_f64(out), ref, what="pasa_forward")
+
+
 def test_forward_convenience_wrapper(P):
     q, k, v = _inputs((4, 16, 16), 2, 64)
     out, idx = P.forward(q, k, v, keep_ratio=0.25, seed=5, noise_amp=0.2)
