@@ -56,7 +56,7 @@ extern "C" {
 typedef enum {
   PASA_OK = 0,
   PASA_EINVAL = -1,       /* null pointer, non-positive size, ratio outside (0,1], k outside [1,N_B] */
-  PASA_EUNSUPPORTED = -2, /* d, block or group not supported                                          */
+  PASA_EUNSUPPORTED = -2, /* d, block, group or slicing not supported; a size limit exceeded                  */
   PASA_EWORKSPACE = -3,   /* workspace smaller than pasa_*_workspace_bytes says                        */
   PASA_EALIGN = -4,       /* pointer not 16-byte aligned / stride not a multiple of 8 elements         */
   PASA_EHIP = -5,         /* the HIP runtime refused a launch                                          */
@@ -77,8 +77,9 @@ typedef struct {
   int32_t kv_slices; /* tuning knob of pasa_sparse_attn_fwd: the key range is cut into this many
                     contiguous slices, slice s is walked by workgroups of XCD s % 8 only (so that a
                     slice of K and V stays resident in that XCD's L2) and the per-slice partial results
-                    are merged by a second kernel.  0 = the library chooses; 1 = no slicing; otherwise
-                    a multiple of 8 not above ceil(N_B / 32).  Results do not depend on it beyond
+                    are merged by a second kernel.  0 = the library chooses (today: no slicing, which is
+                    faster at every shape measured); 1 = no slicing; otherwise a multiple of 8 not above
+                    ceil(N_B / 32).  Results do not depend on it beyond
                     floating-point summation order.                                               */
 } pasa_shape_t;
 
@@ -97,11 +98,12 @@ PASA_API int32_t pasa_num_blocks(const pasa_shape_t* shape);
 /* host-only.  Number of uint32 words of one row of the selection bitmap: ceil(N_B / 32). */
 PASA_API int32_t pasa_mask_words(int32_t n_blocks);
 
-/* host-only.  Bytes of scratch pasa_block_score needs (pooled Q and K in fp32); 0 on a bad shape. */
+/* host-only.  Bytes of scratch pasa_block_score needs (block means of Q and K, 4 bytes per element); 0 on a bad shape. */
 PASA_API size_t pasa_score_workspace_bytes(const pasa_shape_t* shape);
 
-/* host-only.  Bytes of scratch pasa_sparse_attn_fwd and pasa_attn_dense_ref need (key/value block statistics,
- * group matrices, room for a selection bitmap; with kv_slices > 1 also the per-slice partial results:
+/* host-only.  Bytes of scratch pasa_kv_stats, pasa_sparse_attn_fwd and pasa_attn_dense_ref need (key/value block
+ * statistics, group matrices and unit sums, block-mean keys for pasa_block_score_with_stats, room for a selection
+ * bitmap: 0.20 GB at 40 heads of 75,600 tokens; with kv_slices > 1 also the per-slice partial results:
  * B*H*kv_slices*n*(d+2)*4 bytes, 12.6 GB at 40 heads of 75,600 tokens with 8 slices); 0 on a bad shape. */
 PASA_API size_t pasa_attn_workspace_bytes(const pasa_shape_t* shape);
 
