@@ -236,3 +236,22 @@ def test_binding_checks_that_the_strides_stay_inside_the_tensors():
     mod._check_extent(mod.Shape.of(view), q=view)
     with pytest.raises(ValueError, match="bf16"):
         mod._check_extent(shape, q=q.float())
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/pasa.h compiles as C99 with no HIP header in sight, and a C program links against the library by name"""
+    import subprocess
+    src = tmp_path / "use_pasa.c"
+    src.write_text('#include "pasa.h"\n#include <stdio.h>\n'
+                   'int main(void) { pasa_shape_t s = {1, 2, 1000, 128, 64, 32, 256000, 128000, 128, 0.0f, 0};\n'
+                   '  printf("%d %d %zu %s\\n", pasa_num_blocks(&s), pasa_topk_count(16, 0.25), pasa_attn_workspace_bytes(&s) > 0 ? (size_t)1 : (size_t)0,'
+                   ' pasa_strerror(PASA_ESCRATCH));\n  return 0; }\n')
+    inc = os.path.join(ROOT, "include")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-fsyntax-only", "-I", inc, str(src)], check=True)
+    import paper_2604_12219_amd as P
+    exe = tmp_path / "use_pasa"
+    libdir = os.path.dirname(P.lib_path())
+    subprocess.run(["gcc", "-std=c99", "-I", inc, str(src), "-o", str(exe), "-L", libdir, "-l:libpasa_hip.so", f"-Wl,-rpath,{libdir}"],
+                   check=True)
+    out = subprocess.run([str(exe)], capture_output=True, text=True, check=True).stdout.split(maxsplit=3)
+    assert out[:3] == ["16", "4", "1"] and "static" in out[3]
